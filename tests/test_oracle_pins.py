@@ -1,0 +1,363 @@
+"""Pins for the CPU oracle (oracle/fc_oracle.c): everything here runs without a GPU.
+
+P0  hand-worked traces of Algorithm 1 (tests/golden/alg1_handworked.json)
+P1  array-op rendering of Algorithm 1 (tests/alg1_arrayops.py) on tiny tables, random traces
+P2  cache transparency: flushed table == EmbeddingBag-sum + SGD on the whole table, no cache
+    (Section 2.2: updates are synchronous, so the cache must be invisible)
+P3  closed form for config 1 (all-ones gradient, one id per bag)
+P4  special cases of the policy
+I1-I6 invariants (maps inverse, residency, conservation, inclusion in cache size, ...)
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import Oracle, OracleError
+from tests.alg1_arrayops import ArrayOpsCache
+from workloads import make_workload, table_values
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def one_hot_offsets(n):
+    return np.arange(n + 1, dtype=np.int64)
+
+
+def rand_table(N, D, seed=0):
+    return table_values(seed, np.arange(N), D).copy()
+
+
+def check_maps(o: Oracle):
+    sr, rs = o.slot_rank, o.rank_slot
+    res = sr[sr >= 0]
+    assert len(np.unique(res)) == len(res), "I1: duplicate row in cache"
+    assert (rs[res] == np.nonzero(sr >= 0)[0]).all(), "I1: rank_slot[slot_rank[s]] != s"
+    on = np.nonzero(rs >= 0)[0]
+    assert (sr[rs[on]] == on).all(), "I1: slot_rank[rank_slot[u]] != u"
+    assert len(on) == len(res)
+    assert ((sr >= 0) | (sr == -1)).all()
+
+
+# ---------------------------------------------------------------- P0
+def test_handworked_traces():
+    g = json.load(open(os.path.join(HERE, "golden", "alg1_handworked.json")))
+    N, C = g["num_rows"], g["cache_rows"]
+    fr = np.array(g["freq_rank"], dtype=np.int32)
+    for tr in g["traces"]:
+        host = rand_table(N, 4)
+        o = Oracle(fr, host, C, warm=tr["warm"])
+        for b in tr["batches"]:
+            ids = np.array(b["ids"], dtype=np.int64)
+            assert list(fr[ids]) == b["ranks"]
+            slots = o.prepare(ids, one_hot_offsets(len(ids)))
+            L, s = o.last_lists(), o.stats()
+            assert list(L["miss_ranks"]) == b["miss_ranks"]
+            assert list(L["evict_ranks"]) == b["evict_ranks"]
+            assert list(L["fill_slots"]) == b["fill_slots"]
+            assert list(o.slot_rank) == b["slot_rank_after"]
+            assert list(slots) == b["slots"]
+            assert s["n_hit_ids"] == b["n_hit_ids"] and s["n_unique"] == b["n_unique"]
+            assert s["bytes_h2d"] == len(b["miss_ranks"]) * 4 * 4
+            assert s["bytes_d2h"] == len(b["evict_ranks"]) * 4 * 4
+            check_maps(o)
+
+
+# ---------------------------------------------------------------- P1
+@pytest.mark.parametrize("seed", range(12))
+def test_against_array_ops_algorithm1(seed):
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(6, 64))
+    C = int(rng.integers(1, min(N, 9) + 1))
+    D = 3
+    warm = bool(seed % 2)
+    fr = rng.permutation(N).astype(np.int32)
+    host_a = rand_table(N, D, seed)
+    host_b = host_a.copy()
+    o = Oracle(fr, host_a, C, warm=warm)
+    ref = ArrayOpsCache(fr, host_b, C, warm=warm)
+    for t in range(40):
+        kind = t % 5
+        if kind == 0:      # exactly C distinct rows: the whole cache is needed
+            ids = rng.permutation(N)[:C]
+        elif kind == 1:    # all hits: rows currently resident (or a cold start)
+            res = np.nonzero(o.rank_slot >= 0)[0]
+            ids = np.argsort(fr)[res][: max(1, C // 2)] if len(res) else rng.integers(0, N, size=1)
+        else:
+            k = int(rng.integers(1, C + 1))
+            ids = rng.permutation(N)[:k]
+            ids = np.concatenate([ids, ids[rng.integers(0, k, size=int(rng.integers(0, 4)))]])  # duplicates
+            rng.shuffle(ids)
+        ids = ids.astype(np.int64)
+        # perturb resident rows so that write-back moves distinguishable data
+        slots_ref = ref.prepare_cache(ids)
+        slots = o.prepare(ids, one_hot_offsets(len(ids)))
+        L, s = o.last_lists(), o.stats()
+        assert np.array_equal(slots, slots_ref)
+        assert np.array_equal(o.slot_rank, ref.cache_idx_map)
+        assert np.array_equal(L["miss_ranks"], ref.missed)
+        assert np.array_equal(L["evict_ranks"], ref.evicted)
+        assert np.array_equal(L["fill_slots"], ref.targets)
+        assert s["n_hit_ids"] == ref.hit_ids
+        assert s["n_miss"] == len(ref.missed) and s["n_evict"] == len(ref.evicted)
+        assert s["n_hit_unique"] == s["n_unique"] - s["n_miss"]
+        check_maps(o)
+        # update cached rows identically on both sides (same slots): a fake optimizer step
+        g = rng.standard_normal((len(ids), D)).astype(np.float32)
+        o.embedding_bag_bwd_sgd(slots, one_hot_offsets(len(ids)), g, 0.5)
+        acc = np.zeros_like(ref.cuda_weight)
+        for i, sl in enumerate(slots_ref):
+            acc[sl] = acc[sl] + g[i]
+        for sl in np.unique(slots_ref):
+            ref.cuda_weight[sl] = ref.cuda_weight[sl] - np.float32(0.5) * acc[sl]
+        assert np.array_equal(o.cache, ref.cuda_weight)
+        assert np.array_equal(host_a, host_b)
+
+
+# ---------------------------------------------------------------- P2
+def no_cache_training(W, batches, lr):
+    """EmbeddingBag(sum) + SGD on the full table in id space, lookups accumulated in position order."""
+    outs = []
+    for ids, offsets, grad in batches:
+        B = len(offsets) - 1
+        out = np.zeros((B, W.shape[1]), dtype=np.float32)
+        g = {}
+        for b in range(B):
+            for i in range(offsets[b], offsets[b + 1]):
+                out[b] = out[b] + W[ids[i]]
+        for b in range(B):
+            for i in range(offsets[b], offsets[b + 1]):
+                k = int(ids[i])
+                g[k] = (g[k] + grad[b]) if k in g else (np.zeros(W.shape[1], np.float32) + grad[b])
+        for k, gk in g.items():
+            W[k] = W[k] - np.float32(lr) * gk
+        outs.append(out)
+    return outs
+
+
+def random_bags(rng, N, C, multi):
+    if multi:
+        B = int(rng.integers(1, 6))
+        sizes = rng.integers(0, 4, size=B)
+        n = int(sizes.sum())
+        offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    else:
+        n = int(rng.integers(1, C + 3))
+        offsets = one_hot_offsets(n)
+    pool = rng.permutation(N)[: max(1, min(C, n))]
+    ids = pool[rng.integers(0, len(pool), size=n)].astype(np.int64)
+    return ids, offsets
+
+
+@pytest.mark.parametrize("seed,warm,multi", [(s, w, m) for s in range(4) for w in (0, 1) for m in (0, 1)])
+def test_cache_is_transparent(seed, warm, multi):
+    rng = np.random.default_rng(100 + seed)
+    N, D = 50, 5
+    C = int(rng.integers(3, 12))
+    fr = rng.permutation(N).astype(np.int32)
+    inv = np.argsort(fr)
+    W = rand_table(N, D, seed)                 # id space
+    host = W[inv].copy()                       # rank space: row rho = W[id with rank rho]
+    o = Oracle(fr, host, C, warm=bool(warm))
+    batches = []
+    for t in range(30):
+        ids, offsets = random_bags(rng, N, C, multi)
+        grad = rng.standard_normal((len(offsets) - 1, D)).astype(np.float32)
+        batches.append((ids, offsets, grad))
+    W_ref = W.copy()
+    outs_ref = no_cache_training(W_ref, batches, 0.1)
+    for (ids, offsets, grad), out_ref in zip(batches, outs_ref):
+        slots = o.prepare(ids, offsets)
+        out = o.embedding_bag_fwd(slots, offsets)
+        assert np.array_equal(out, out_ref)          # same fp32 operations in the same order
+        o.embedding_bag_bwd_sgd(slots, offsets, grad, 0.1)
+        check_maps(o)
+    o.flush()
+    assert np.array_equal(host, W_ref[inv])          # I3: host + cache == full table after flush
+
+
+def test_values_against_torch_embedding_bag_autograd():
+    """Same as P2 but the reference is the library routine: torch EmbeddingBag(sum) + autograd + SGD."""
+    rng = np.random.default_rng(7)
+    N, D, C = 200, 8, 20
+    fr = rng.permutation(N).astype(np.int32)
+    inv = np.argsort(fr)
+    W = rand_table(N, D, 3)
+    host = W[inv].copy()
+    o = Oracle(fr, host, C, warm=True)
+    Wt = torch.tensor(W, dtype=torch.float64, requires_grad=True)
+    for t in range(25):
+        B = 12
+        sizes = rng.integers(0, 5, size=B)
+        offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        pool = rng.permutation(N)[:C]
+        ids = pool[rng.integers(0, C, size=int(sizes.sum()))].astype(np.int64)
+        grad = rng.standard_normal((B, D)).astype(np.float32)
+        slots = o.prepare(ids, offsets)
+        out = o.embedding_bag_fwd(slots, offsets)
+        o.embedding_bag_bwd_sgd(slots, offsets, grad, 0.05)
+        out_t = torch.nn.functional.embedding_bag(torch.tensor(ids), Wt, torch.tensor(offsets[:-1]), mode="sum")
+        np.testing.assert_allclose(out, out_t.detach().numpy(), rtol=1e-5, atol=1e-7)
+        out_t.backward(torch.tensor(grad, dtype=torch.float64))
+        with torch.no_grad():
+            Wt -= 0.05 * Wt.grad
+            Wt.grad.zero_()
+    o.flush()
+    np.testing.assert_allclose(host, Wt.detach().numpy()[inv], rtol=1e-5, atol=1e-6)
+
+
+# ---------------------------------------------------------------- P3
+@pytest.mark.parametrize("warm", [True, False])
+def test_config1_closed_form(warm):
+    w = make_workload("c1")
+    host = w.host_table()
+    W0 = host.copy()
+    o = Oracle(w.freq_rank, host, w.cache_rows, warm=warm)
+    count = np.zeros(w.num_rows, dtype=np.int64)
+    hits = tot = 0
+    for t in range(w.num_batches):
+        ids, offsets = w.batch(t)
+        slots = o.prepare(ids, offsets)
+        s = o.stats()
+        hits += s["n_hit_ids"]
+        tot += s["n_ids"]
+        o.embedding_bag_fwd(slots, offsets)
+        o.embedding_bag_bwd_sgd(slots, offsets, w.grad(t, len(offsets) - 1), w.lr)
+        np.add.at(count, w.freq_rank[ids], 1)
+    o.flush()
+    expect = W0.astype(np.float64) - 0.01 * count[:, None]
+    np.testing.assert_allclose(host, expect, rtol=1e-4, atol=1e-6)
+    assert 0.5 < hits / tot < 0.95        # skewed ids: most lookups hit a 1.5% cache (Section 3)
+
+
+# ---------------------------------------------------------------- P4
+def test_full_size_cache_never_misses():
+    N, D = 40, 2
+    rng = np.random.default_rng(1)
+    fr = rng.permutation(N).astype(np.int32)
+    host = rand_table(N, D)
+    o = Oracle(fr, host, N, warm=True)
+    for t in range(5):
+        ids = rng.integers(0, N, size=30).astype(np.int64)
+        slots = o.prepare(ids, one_hot_offsets(30))
+        s = o.stats()
+        assert s["n_miss"] == 0 and s["n_evict"] == 0 and s["n_hit_ids"] == 30
+        assert np.array_equal(slots, fr[ids])      # warm-up puts cpu_row_idx s into slot s
+
+
+def test_cold_cache_large_enough_only_first_touch_misses():
+    N, D, C = 100, 2, 60
+    rng = np.random.default_rng(2)
+    fr = rng.permutation(N).astype(np.int32)
+    o = Oracle(fr, rand_table(N, D), C, warm=False)
+    pool = rng.permutation(N)[:C]
+    seen = set()
+    for t in range(20):
+        ids = pool[rng.integers(0, C, size=25)].astype(np.int64)
+        o.prepare(ids, one_hot_offsets(25))
+        s = o.stats()
+        new = set(ids.tolist()) - seen
+        assert s["n_miss"] == len(new) and s["n_evict"] == 0
+        seen |= new
+
+
+def test_first_warm_batch_hits_are_top_ranks():
+    w = make_workload("c2", scale=0.01, cache_ratio=0.05)
+    o = Oracle(w.freq_rank, w.host_table(), w.cache_rows, warm=True)
+    ids, offsets = w.batch(0)
+    o.prepare(ids, offsets)
+    r = np.unique(w.freq_rank[ids])
+    L = o.last_lists()
+    assert np.array_equal(L["miss_ranks"], r[r >= w.cache_rows])
+    # LFU by static rank: victims are exactly the largest resident ranks not used by the batch
+    resident_unused = np.setdiff1d(np.arange(w.cache_rows), r)
+    assert np.array_equal(L["evict_ranks"], resident_unused[len(resident_unused) - len(L["evict_ranks"]):])
+
+
+def test_victims_have_largest_rank_and_batch_rows_protected():
+    rng = np.random.default_rng(5)
+    N, C = 300, 40
+    fr = rng.permutation(N).astype(np.int32)
+    o = Oracle(fr, rand_table(N, 2), C, warm=True)
+    for t in range(50):
+        ids = rng.integers(0, N, size=int(rng.integers(1, C))).astype(np.int64)
+        before = o.slot_rank
+        o.prepare(ids, one_hot_offsets(len(ids)))
+        U = np.unique(fr[ids])
+        L, s = o.last_lists(), o.stats()
+        ev = L["evict_ranks"]
+        free_before = int((before == -1).sum())
+        assert len(ev) == max(0, s["n_miss"] - free_before)          # I2: |V| = need
+        assert len(np.intersect1d(ev, U)) == 0                       # protected
+        still = np.setdiff1d(before[before >= 0], np.concatenate([ev, U]))
+        if len(ev) and len(still):
+            assert ev.min() > still.max()                            # every victim ranks below every survivor
+        assert (o.rank_slot[fr[ids]] >= 0).all()                     # I2: all rows of the batch resident
+        res_before, res_after = int((before >= 0).sum()), int((o.slot_rank >= 0).sum())
+        assert res_after == res_before + s["n_miss"] - s["n_evict"]  # I5
+        assert s["bytes_h2d"] + s["bytes_d2h"] == (s["n_miss"] + s["n_evict"]) * 2 * 4
+
+
+# ---------------------------------------------------------------- I4
+@pytest.mark.parametrize("warm", [True, False])
+def test_resident_set_inclusion_in_cache_size(warm):
+    """Priority (in current batch, then static rank) does not depend on C, so the resident set at C is a
+    subset of the resident set at C' > C after every batch; hit counts are therefore monotone in C."""
+    w = make_workload("c2", scale=0.003)
+    sizes = sorted([w.samples * 26 + 8, w.samples * 26 * 2, w.samples * 26 * 4, w.num_rows // 3])
+    host = w.host_table()
+    orcs = [Oracle(w.freq_rank, host.copy(), c, warm=warm) for c in sizes]
+    hits = [0] * len(sizes)
+    for t in range(25):
+        ids, offsets = w.batch(t)
+        prev = None
+        for k, o in enumerate(orcs):
+            o.prepare(ids, offsets)
+            hits[k] += o.stats()["n_hit_ids"]
+            res = set(np.nonzero(o.rank_slot >= 0)[0].tolist())
+            if prev is not None:
+                assert prev <= res
+            prev = res
+    assert hits == sorted(hits)
+
+
+# ---------------------------------------------------------------- error paths
+def test_error_paths_leave_state_unchanged():
+    rng = np.random.default_rng(3)
+    N, C, D = 30, 5, 2
+    fr = rng.permutation(N).astype(np.int32)
+    host = rand_table(N, D)
+    o = Oracle(fr, host, C, warm=True)
+    o.prepare(np.array([3, 4, 5], dtype=np.int64), one_hot_offsets(3))
+    sr, rs, ca, ho = o.slot_rank, o.rank_slot, o.cache, host.copy()
+
+    def unchanged():
+        return (np.array_equal(sr, o.slot_rank) and np.array_equal(rs, o.rank_slot)
+                and np.array_equal(ca, o.cache) and np.array_equal(ho, host))
+
+    with pytest.raises(OracleError) as e:
+        o.prepare(np.arange(C + 1, dtype=np.int64), one_hot_offsets(C + 1))
+    assert e.value.name == "BATCH_EXCEEDS_CACHE" and unchanged()
+    with pytest.raises(OracleError) as e:
+        o.prepare(np.array([1, N], dtype=np.int64), one_hot_offsets(2))
+    assert e.value.name == "ID_OUT_OF_RANGE" and unchanged()
+    with pytest.raises(OracleError) as e:
+        o.prepare(np.array([1, -1], dtype=np.int64), one_hot_offsets(2))
+    assert e.value.name == "ID_OUT_OF_RANGE" and unchanged()
+    for bad in ([0, 2, 1, 3], [1, 2, 3], [0, 1, 2]):
+        with pytest.raises(OracleError) as e:
+            o.prepare(np.array([1, 2, 3], dtype=np.int64), np.array(bad, dtype=np.int64))
+        assert e.value.name == "BAD_OFFSETS" and unchanged()
+    with pytest.raises(OracleError) as e:
+        Oracle(np.zeros(N, dtype=np.int32), host, C)
+    assert e.value.name == "NOT_PERMUTATION"
+    for c in (0, N + 1):
+        with pytest.raises(OracleError):
+            Oracle(fr, host, c)
+    # empty batch and empty bags are fine
+    slots = o.prepare(np.empty(0, dtype=np.int64), np.zeros(4, dtype=np.int64))
+    assert len(slots) == 0 and unchanged()
+    out = o.embedding_bag_fwd(slots, np.zeros(4, dtype=np.int64))
+    assert out.shape == (3, D) and (out == 0).all()

@@ -1,0 +1,169 @@
+/* freqcache -- C ABI of the MI355X (gfx950) frequency-aware software cache for large
+ * embedding tables, after arXiv:2208.05321 ("A Frequency-aware Software Cache for Large
+ * Recommendation System Embeddings").
+ *
+ * The library keeps the whole embedding table in pinned host memory, re-ordered by
+ * descending id frequency ("CPU Weight", paper Section 4.2), and `cache_rows` of its rows
+ * in HBM ("CUDA Cached Weight", Section 4.3).  Once per training iteration the caller
+ * turns the batch's ids into row indices of the cached weight (Algorithm 1,
+ * PrepareCache), runs the EmbeddingBag-sum forward on the cached rows and applies the
+ * sparse SGD update to them (Section 4.3, last step of the workflow; synchronous
+ * updates, Section 2.2).  Every step runs in hand-written HIP kernels on the caller's
+ * stream; a second, library-owned stream carries the write-back of evicted rows.
+ *
+ * Conventions
+ *   - every function returns FC_OK (0) or a negative FC_ERR_* code; nothing throws or aborts;
+ *   - pointers named *_dev are device pointers owned by the caller (e.g. PyTorch tensors),
+ *     pointers named *_host are ordinary host pointers owned by the caller;
+ *   - one handle = one table = one GPU (the device current at cache_create); a handle is
+ *     not thread-safe and calls on one handle must not overlap;
+ *   - ids are already offset into the single concatenated table (Section 5.1);
+ *   - int32 row indices internally: num_rows < 2^31 - 2^16, n < 2^31 - 2^16.
+ *
+ * There is no CPU fallback: if no HIP device is usable the calls fail with FC_ERR_HIP.
+ */
+#ifndef FREQCACHE_H
+#define FREQCACHE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fc_cache fc_cache; /* opaque, owned by the library */
+
+/* Observables of the most recent successful cache_prepare (Algorithm 1). */
+typedef struct fc_stats {
+    int64_t n_ids;        /* ids in the batch                                            */
+    int64_t n_unique;     /* distinct rows the batch touches (|unique(idx_map[ids])|)    */
+    int64_t n_hit_unique; /* of those, already resident                                  */
+    int64_t n_hit_ids;    /* ids whose row was already resident (access-level hits)      */
+    int64_t n_miss;       /* rows moved host -> HBM                                      */
+    int64_t n_evict;      /* rows moved HBM -> host                                      */
+    int64_t bytes_h2d;    /* n_miss  * dim * 4                                           */
+    int64_t bytes_d2h;    /* n_evict * dim * 4                                           */
+} fc_stats;
+
+enum {
+    FC_OK = 0,
+    FC_ERR_INVALID_ARG = -1,
+    FC_ERR_ID_OUT_OF_RANGE = -2,     /* an id outside [0, num_rows)                               */
+    FC_ERR_BAD_OFFSETS = -3,         /* offsets[0] != 0, offsets[num_bags] != n, or not monotone  */
+    FC_ERR_BATCH_EXCEEDS_CACHE = -4, /* more distinct rows in the batch than cache_rows           */
+    FC_ERR_NOT_PERMUTATION = -5,     /* freq_rank is not a permutation of [0, num_rows)           */
+    FC_ERR_OOM_DEVICE = -6,
+    FC_ERR_OOM_PINNED = -7,
+    FC_ERR_HIP = -8,                 /* a HIP runtime call failed, or no usable device            */
+    FC_ERR_NOT_PINNED = -9,          /* host_weight given but not page-locked, GPU-mapped memory  */
+    FC_ERR_BAD_SLOT = -10            /* a slot index outside [0, cache_rows) reached fwd / bwd     */
+};
+
+/* cache_create flags */
+enum {
+    FC_WARM = 1,            /* preload the cache_rows highest-frequency rows (Section 4.3, "cache warm-up") */
+    FC_TRANSMIT_STAGED = 2  /* move rows the way the paper's data transmitter does (Section 4.3):
+                               gather into a contiguous block on the source side, one bulk
+                               hipMemcpyAsync over the host link, scatter on the target side.
+                               Default (flag clear): kernels read / write the mapped pinned table
+                               directly, one row-group of lanes per row.  Results are identical. */
+};
+
+/* Static module + dynamic module set-up (Sections 4.2, 4.3).
+ *   num_rows, dim   table shape; fp32; dim >= 1.
+ *   cache_rows      rows of the cached weight, 0 < cache_rows <= num_rows (the paper's cache ratio
+ *                   times num_rows; 1.5% by default there).
+ *   freq_rank_host  "idx_map": id -> row of the frequency-ordered table (0 = most frequent).
+ *                   Host pointer, length num_rows, must be a permutation; copied.
+ *   host_weight     the frequency-ordered table, num_rows*dim fp32, row r = embedding of the id with
+ *                   rank r.  Either NULL -- the library allocates pinned memory, the caller fills it
+ *                   through cache_host_weight() BEFORE the first cache_prepare (and before
+ *                   cache_create's warm-up if FC_WARM is wanted: then create cold, fill, and call
+ *                   cache_warm) -- or a pointer to page-locked, GPU-mapped memory
+ *                   (hipHostMalloc / a pinned torch tensor) that outlives the handle.  The table is
+ *                   the store of record: evictions and cache_flush write into it.
+ *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3, "the memory
+ *                   footprint of the data transmitter is strictly limited"); larger transfers are
+ *                   done in several rounds.  0 = default (min(cache_rows, 131072)).
+ *   flags           FC_WARM | FC_TRANSMIT_STAGED.
+ *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
+ *   out             receives the handle.
+ * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous. */
+int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_t* freq_rank_host,
+                 float* host_weight, int64_t staging_rows, int32_t flags, void* hip_stream, fc_cache** out);
+
+/* Cache warm-up (Section 4.3): empty the cache and load rows 0..cache_rows-1 of the host table into
+ * slots 0..cache_rows-1.  cache_create(FC_WARM) calls this.  Synchronous.  Does not write back
+ * resident rows first (call cache_flush if they carry updates). */
+int cache_warm(fc_cache* c);
+
+/* Algorithm 1 (PrepareCache + PrepareCPURowIdxOnGPU): make every row the batch needs resident and
+ * return, per input id, its row index in the cached weight.
+ *   ids_dev      int64[n], device.           offsets_dev  int64[num_bags+1], device, bag b = ids
+ *   slots_dev    int32[n], device, output.                [offsets[b], offsets[b+1]) (EmbeddingBag).
+ * Steps, all on the GPU: ids -> frequency rank; distinct ranks; split into resident / missing; if the
+ * missing rows outnumber the empty slots, evict that many resident rows not used by this batch,
+ * largest rank (least frequent) first, writing them back to the host table; assign the i-th smallest
+ * missing rank to the i-th smallest empty slot and load it from the host table.
+ * On return the index decisions are final and the error code is known (the call waits for the
+ * planning kernels, a few microseconds of GPU work); row movement and the slot write-out are enqueued
+ * on the stream, so later work on the same stream sees every needed row resident.
+ * Errors: INVALID_ARG, BAD_OFFSETS, ID_OUT_OF_RANGE, BATCH_EXCEEDS_CACHE (in this order of precedence),
+ * OOM_DEVICE, HIP.  On any error the cache state is unchanged and slots_dev is unspecified. */
+int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                  int32_t* slots_dev);
+
+/* EmbeddingBag, mode "sum", on the cached weight (Section 4.3: the framework's embedding op runs on the
+ * cached weight after the cache step):  out[b, :] = sum_{i in bag b} cached_weight[slots[i], :], summed
+ * in position order; an empty bag gives zeros.
+ *   slots_dev int32[n] as returned by the latest cache_prepare; out_dev fp32[num_bags*dim], device.
+ * Asynchronous on the stream.  A slot outside [0, cache_rows) contributes nothing and raises a sticky
+ * FC_ERR_BAD_SLOT reported by cache_check. */
+int embedding_bag_fwd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
+                      int64_t num_bags, float* out_dev);
+
+/* Backward of the sum-bag fused with the SGD step (synchronous update, Section 2.2): for every distinct
+ * slot s, g = sum over the lookups i with slots[i] == s of grad_out[bag(i), :] (a row looked up k times
+ * receives k gradients), then cached_weight[s, :] -= lr * g.  Deterministic: no floating-point atomics;
+ * lookups of a slot are summed in position order within fixed blocks of consecutive lookups.
+ *   grad_out_dev fp32[num_bags*dim], device.  Asynchronous on the stream; BAD_SLOT as above. */
+int embedding_bag_bwd_sgd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
+                          int64_t num_bags, const float* grad_out_dev, float lr);
+
+/* Write every resident row back to the host table (the host table is the store of record, Section 3);
+ * residency is unchanged.  Returns after the host table is complete. */
+int cache_flush(fc_cache* c);
+
+/* Wait for all enqueued work of this handle and return the sticky asynchronous error, if any
+ * (then clears it). */
+int cache_check(fc_cache* c);
+
+/* Waits for outstanding work, frees everything the library allocated.  Does NOT flush. */
+int cache_destroy(fc_cache* c);
+
+/* ---- introspection (parity checks, reports) ---- */
+int cache_last_stats(const fc_cache* c, fc_stats* out);
+/* Copies of the two index maps (paper's cache_idx_map in both directions): slot_rank_host int32[cache_rows]
+ * (-1 = empty slot), rank_slot_host int32[num_rows] (-1 = not resident); either may be NULL. Synchronous. */
+int cache_copy_state(fc_cache* c, int32_t* slot_rank_host, int32_t* rank_slot_host);
+/* Lists of the latest cache_prepare, each may be NULL: missing ranks (ascending, n_miss), evicted ranks
+ * (ascending, n_evict) with the slots they left, and fill_slots[j] = slot that received miss_ranks[j]. */
+int cache_last_lists(fc_cache* c, int32_t* miss_ranks_host, int32_t* evict_ranks_host, int32_t* evict_slots_host,
+                     int32_t* fill_slots_host);
+/* Copy of the cached weight, fp32[cache_rows*dim]. Synchronous. */
+int cache_copy_rows(fc_cache* c, float* rows_host);
+/* The pinned, frequency-ordered host table (library- or caller-allocated). */
+float* cache_host_weight(fc_cache* c);
+const char* cache_strerror(int code);
+
+/* ---- per-kernel timing with HIP events on the handle's own streams (for the benchmark) ---- */
+int cache_profile_enable(fc_cache* c, int32_t on);   /* on=1 starts recording, 0 stops; resets totals when turned on */
+int cache_profile_count(void);                        /* number of timed kernels / copies                               */
+const char* cache_profile_name(int32_t k);
+/* total milliseconds and number of launches of timed item k since profiling was enabled; synchronises */
+int cache_profile_get(fc_cache* c, int32_t k, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREQCACHE_H */

@@ -1,0 +1,350 @@
+// C-ABI entry points of the freqcache library: set-up, warm-up, flush, introspection, profiling.
+// The per-batch work lives in fc_prepare.hip (Algorithm 1) and fc_embedding.hip (EmbeddingBag + SGD).
+#include "fc_internal.h"
+
+#include <new>
+#include <string.h>
+#include <vector>
+
+namespace fc {
+
+// ---- profiling ----
+static const char* const kProfNames[P_COUNT] = {
+    "remap_mark", "rank_count", "rank_plan", "rank_emit", "evict_gather", "evict_store", "free_pick",
+    "miss_fill", "slots_out", "bag_fwd", "sort_hist", "sort_scan", "sort_scatter", "bwd_reduce", "bwd_fixup",
+    "h2d_block", "d2h_block", "flush_rows"};
+
+ProfScope::ProfScope(fc_cache* c_, int item_, hipStream_t s_) : c(c_), s(s_), item(item_) {
+    if (!c->prof_on) return;
+    for (hipEvent_t* e : {&a, &b}) {
+        if (!c->ev_pool.empty()) { *e = c->ev_pool.back(); c->ev_pool.pop_back(); }
+        else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }
+    }
+    if (a) (void)hipEventRecord(a, s);
+}
+ProfScope::~ProfScope() {
+    if (!a || !b) return;
+    (void)hipEventRecord(b, s);
+    c->spans.push_back({item, a, b});
+}
+void prof_collect(fc_cache* c) {
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipStreamSynchronize(c->side);
+    for (const ProfSpan& sp : c->spans) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) { c->prof_ms[sp.item] += ms; c->prof_n[sp.item] += 1; }
+        c->ev_pool.push_back(sp.a);
+        c->ev_pool.push_back(sp.b);
+    }
+    c->spans.clear();
+}
+
+// ---- state initialisation ----
+__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+// first `count` entries: identity, rest -1
+__global__ void k_iota_or_neg(int32_t* p, int64_t n, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = i < count ? (int32_t)i : -1;
+}
+// bitmap with the first `count` bits set
+__global__ void k_bits_prefix(uint32_t* p, int64_t words, int64_t count) {
+    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < words; w += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t lo = w * 32;
+        uint32_t v = 0;
+        if (count >= lo + 32) v = 0xFFFFFFFFu;
+        else if (count > lo) v = (1u << (count - lo)) - 1u;
+        p[w] = v;
+    }
+}
+__global__ void k_set_ctl(Ctl* ctl, int nfree) {
+    ctl->err_flags = 0; ctl->async_flags = 0; ctl->hit_ids = 0; ctl->nfree = nfree;
+    ctl->status = 0; ctl->n_unique = 0; ctl->n_miss = 0; ctl->need = 0;
+}
+
+static int reset_state(fc_cache* c, bool warm) {
+    hipStream_t st = c->stream;
+    const int64_t words = c->NB * RT_WORDS;
+    k_iota_or_neg<<<1024, 256, 0, st>>>(c->rank_slot, c->N, warm ? c->C : 0);
+    k_iota_or_neg<<<256, 256, 0, st>>>(c->slot_rank, c->C, warm ? c->C : 0);
+    k_bits_prefix<<<256, 256, 0, st>>>(c->ubits, words, 0);
+    k_bits_prefix<<<256, 256, 0, st>>>(c->rbits, words, warm ? c->C : 0);
+    k_bits_prefix<<<64, 256, 0, st>>>(c->fbits, c->CW, warm ? 0 : c->C);
+    k_set_ctl<<<1, 1, 0, st>>>(c->ctl, warm ? 0 : (int)c->C);
+    FC_HIP(hipGetLastError());
+    if (warm) FC_HIP(hipMemcpyAsync(c->cache, c->host, (size_t)c->C * c->D * 4, hipMemcpyHostToDevice, st));
+    else FC_HIP(hipMemsetAsync(c->cache, 0, (size_t)c->C * c->D * 4, st));   // empty slots read as zeros
+    FC_HIP(hipStreamSynchronize(st));
+    c->last = fc_stats{};
+    c->have_lists = false;
+    return FC_OK;
+}
+
+static void destroy(fc_cache* c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    if (c->stream || c->side) (void)hipDeviceSynchronize();
+    for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
+                    (void*)c->rbits, (void*)c->fbits, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
+                    (void*)c->miss_ranks, (void*)c->vrank, (void*)c->vslot, (void*)c->fill_slots, (void*)c->rbuf,
+                    (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->keysA, (void*)c->valsA,
+                    (void*)c->keysB, (void*)c->valsB, (void*)c->ghist, (void*)c->dtot, (void*)c->part, (void*)c->pmeta})
+        if (p) (void)hipFree(p);
+    for (void* p : {(void*)c->hctl, (void*)c->stage_pin, (void*)c->list_pin}) if (p) (void)hipHostFree(p);
+    if (c->own_host && c->host) (void)hipHostFree(c->host);
+    for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp}) if (e) (void)hipEventDestroy(e);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    delete c;
+}
+
+static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float* host_weight, int64_t staging_rows,
+                  int32_t flags, void* hip_stream, fc_cache* c) {
+    FC_HIP(hipGetDevice(&c->device));
+    c->N = N; c->C = C; c->D = D; c->flags = flags;
+    c->stream = (hipStream_t)hip_stream;
+    c->vec = (D % 4 == 0) ? 4 : (D % 2 == 0) ? 2 : 1;
+    const int nv = D / c->vec;
+    c->lpr = 1;
+    while (c->lpr < nv && c->lpr < 64) c->lpr <<= 1;
+    if (staging_rows <= 0) staging_rows = C < 131072 ? C : 131072;
+    if (staging_rows > C) staging_rows = C;
+    c->staging_rows = staging_rows;
+    c->NB = cdiv(cdiv(N, 32), RT_WORDS);
+    c->CW = cdiv(C, 32);
+    const size_t words = (size_t)c->NB * RT_WORDS;
+
+    // host table
+    if (host_weight) {
+        hipPointerAttribute_t attr;
+        hipError_t e = hipPointerGetAttributes(&attr, host_weight);
+        if (e != hipSuccess || attr.type != hipMemoryTypeHost) { (void)hipGetLastError(); return FC_ERR_NOT_PINNED; }
+        c->host = host_weight;
+        c->own_host = false;
+    } else {
+        if (hipHostMalloc((void**)&c->host, (size_t)N * D * 4, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError(); c->host = nullptr; return FC_ERR_OOM_PINNED;
+        }
+        c->own_host = true;
+    }
+    if (hipHostGetDevicePointer((void**)&c->host_dev, c->host, 0) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_NOT_PINNED; }
+
+    FC_HIP(hipMalloc((void**)&c->freq_rank, (size_t)N * 4));
+    FC_HIP(hipMalloc((void**)&c->rank_slot, (size_t)N * 4));
+    FC_HIP(hipMalloc((void**)&c->slot_rank, (size_t)C * 4));
+    FC_HIP(hipMalloc((void**)&c->cache, (size_t)C * D * 4));
+    FC_HIP(hipMalloc((void**)&c->ubits, words * 4));
+    FC_HIP(hipMalloc((void**)&c->rbits, words * 4));
+    FC_HIP(hipMalloc((void**)&c->fbits, (size_t)c->CW * 4));
+    FC_HIP(hipMalloc((void**)&c->bsum, (size_t)c->NB * 3 * 4));
+    FC_HIP(hipMalloc((void**)&c->moff, (size_t)c->NB * 4));
+    FC_HIP(hipMalloc((void**)&c->vtake, (size_t)c->NB * 4));
+    FC_HIP(hipMalloc((void**)&c->voff, (size_t)c->NB * 4));
+    FC_HIP(hipMalloc((void**)&c->miss_ranks, (size_t)C * 4));
+    FC_HIP(hipMalloc((void**)&c->vrank, (size_t)C * 4));
+    FC_HIP(hipMalloc((void**)&c->vslot, (size_t)C * 4));
+    FC_HIP(hipMalloc((void**)&c->fill_slots, (size_t)C * 4));
+    FC_HIP(hipMalloc((void**)&c->ctl, sizeof(Ctl)));
+    FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4));
+    if (hipHostMalloc((void**)&c->hctl, sizeof(HostCtl), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_OOM_PINNED; }
+    memset(c->hctl, 0, sizeof(HostCtl));
+    if (flags & FC_TRANSMIT_STAGED) {
+        FC_HIP(hipMalloc((void**)&c->stage_dev2, (size_t)staging_rows * D * 4));
+        if (hipHostMalloc((void**)&c->stage_pin, (size_t)staging_rows * D * 4, hipHostMallocDefault) != hipSuccess ||
+            hipHostMalloc((void**)&c->list_pin, (size_t)C * 2 * 4, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError(); return FC_ERR_OOM_PINNED;
+        }
+    }
+    FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp})
+        FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
+    return reset_state(c, (flags & FC_WARM) != 0);
+}
+
+}  // namespace fc
+
+using namespace fc;
+
+extern "C" {
+
+int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_t* freq_rank_host, float* host_weight,
+                 int64_t staging_rows, int32_t flags, void* hip_stream, fc_cache** out) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!out) return FC_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || cache_rows <= 0 || cache_rows > num_rows ||
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED)))
+        return FC_ERR_INVALID_ARG;
+    if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
+    {   // idx_map must be a permutation: the host table is the original table re-ordered (Section 4.2)
+        std::vector<uint8_t> seen;
+        try { seen.assign((size_t)num_rows, 0); } catch (const std::bad_alloc&) { return FC_ERR_INVALID_ARG; }
+        for (int64_t i = 0; i < num_rows; ++i) {
+            const int32_t r = freq_rank_host[i];
+            if (r < 0 || r >= num_rows || seen[r]) return FC_ERR_NOT_PERMUTATION;
+            seen[r] = 1;
+        }
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) { (void)hipGetLastError(); return FC_ERR_HIP; }
+    fc_cache* c = new (std::nothrow) fc_cache();
+    if (!c) return FC_ERR_INVALID_ARG;
+    const int rc = create(num_rows, dim, cache_rows, freq_rank_host, host_weight, staging_rows, flags, hip_stream, c);
+    if (rc != FC_OK) { destroy(c); return rc; }
+    *out = c;
+    return FC_OK;
+}
+
+int cache_warm(fc_cache* c) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    FC_HIP(hipStreamSynchronize(c->side));
+    c->evict_pending = false;
+    return reset_state(c, true);
+}
+
+int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                  int32_t* slots_dev) {
+    return prepare_impl(c, ids_dev, n, offsets_dev, num_bags, slots_dev);
+}
+
+int embedding_bag_fwd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                      float* out_dev) {
+    return fwd_impl(c, slots_dev, n, offsets_dev, num_bags, out_dev);
+}
+
+int embedding_bag_bwd_sgd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
+                          int64_t num_bags, const float* grad_out_dev, float lr) {
+    return bwd_impl(c, slots_dev, n, offsets_dev, num_bags, grad_out_dev, lr);
+}
+
+int cache_flush(fc_cache* c) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->side));      // pending evicted rows first: flush must not be overtaken
+    c->evict_pending = false;
+    if (c->flags & FC_TRANSMIT_STAGED) {
+        // the cached weight is contiguous: bulk-copy slot ranges, scatter the resident ones on the host
+        std::vector<int32_t> sr((size_t)c->C);
+        FC_HIP(hipMemcpyAsync(sr.data(), c->slot_rank, (size_t)c->C * 4, hipMemcpyDeviceToHost, c->stream));
+        FC_HIP(hipStreamSynchronize(c->stream));
+        const size_t rowb = (size_t)c->D * 4;
+        for (int64_t s0 = 0; s0 < c->C; s0 += c->staging_rows) {
+            const int64_t rows = c->C - s0 < c->staging_rows ? c->C - s0 : c->staging_rows;
+            {
+                ProfScope ps(c, P_D2H_BLOCK, c->stream);
+                FC_HIP(hipMemcpyAsync(c->stage_pin, c->cache + (size_t)s0 * c->D, rows * rowb, hipMemcpyDeviceToHost, c->stream));
+            }
+            FC_HIP(hipStreamSynchronize(c->stream));
+#pragma omp parallel for schedule(static)
+            for (int64_t j = 0; j < rows; ++j)
+                if (sr[s0 + j] >= 0) memcpy(c->host + (size_t)sr[s0 + j] * c->D, c->stage_pin + (size_t)j * c->D, rowb);
+        }
+        return FC_OK;
+    }
+    FC_TRY(launch_flush_rows(c, c->stream));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    return FC_OK;
+}
+
+int cache_check(fc_cache* c) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    FC_HIP(hipStreamSynchronize(c->side));
+    Ctl h;
+    FC_HIP(hipMemcpy(&h, c->ctl, sizeof(Ctl), hipMemcpyDeviceToHost));
+    if (h.async_flags) {
+        FC_HIP(hipMemset(&c->ctl->async_flags, 0, 4));
+        return FC_ERR_BAD_SLOT;
+    }
+    return FC_OK;
+}
+
+int cache_destroy(fc_cache* c) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    destroy(c);
+    return FC_OK;
+}
+
+int cache_last_stats(const fc_cache* c, fc_stats* out) {
+    if (!c || !out) return FC_ERR_INVALID_ARG;
+    *out = c->last;
+    return FC_OK;
+}
+
+int cache_copy_state(fc_cache* c, int32_t* slot_rank_host, int32_t* rank_slot_host) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    if (slot_rank_host) FC_HIP(hipMemcpy(slot_rank_host, c->slot_rank, (size_t)c->C * 4, hipMemcpyDeviceToHost));
+    if (rank_slot_host) FC_HIP(hipMemcpy(rank_slot_host, c->rank_slot, (size_t)c->N * 4, hipMemcpyDeviceToHost));
+    return FC_OK;
+}
+
+int cache_last_lists(fc_cache* c, int32_t* miss_ranks_host, int32_t* evict_ranks_host, int32_t* evict_slots_host,
+                     int32_t* fill_slots_host) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    if (!c->have_lists) return FC_OK;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    const size_t m = (size_t)c->last.n_miss * 4, v = (size_t)c->last.n_evict * 4;
+    if (miss_ranks_host && m) FC_HIP(hipMemcpy(miss_ranks_host, c->miss_ranks, m, hipMemcpyDeviceToHost));
+    if (fill_slots_host && m) FC_HIP(hipMemcpy(fill_slots_host, c->fill_slots, m, hipMemcpyDeviceToHost));
+    if (evict_ranks_host && v) FC_HIP(hipMemcpy(evict_ranks_host, c->vrank, v, hipMemcpyDeviceToHost));
+    if (evict_slots_host && v) FC_HIP(hipMemcpy(evict_slots_host, c->vslot, v, hipMemcpyDeviceToHost));
+    return FC_OK;
+}
+
+int cache_copy_rows(fc_cache* c, float* rows_host) {
+    if (!c || !rows_host) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->stream));
+    FC_HIP(hipMemcpy(rows_host, c->cache, (size_t)c->C * c->D * 4, hipMemcpyDeviceToHost));
+    return FC_OK;
+}
+
+float* cache_host_weight(fc_cache* c) { return c ? c->host : nullptr; }
+
+const char* cache_strerror(int code) {
+    switch (code) {
+        case FC_OK: return "ok";
+        case FC_ERR_INVALID_ARG: return "invalid argument";
+        case FC_ERR_ID_OUT_OF_RANGE: return "id outside [0, num_rows)";
+        case FC_ERR_BAD_OFFSETS: return "bag offsets do not tile [0, n)";
+        case FC_ERR_BATCH_EXCEEDS_CACHE: return "batch touches more distinct rows than the cache holds";
+        case FC_ERR_NOT_PERMUTATION: return "freq_rank is not a permutation";
+        case FC_ERR_OOM_DEVICE: return "out of device memory";
+        case FC_ERR_OOM_PINNED: return "out of pinned host memory";
+        case FC_ERR_HIP: return "HIP runtime error or no usable GPU";
+        case FC_ERR_NOT_PINNED: return "host_weight is not pinned, GPU-mapped memory";
+        case FC_ERR_BAD_SLOT: return "slot index outside [0, cache_rows)";
+        default: return "unknown error";
+    }
+}
+
+int cache_profile_enable(fc_cache* c, int32_t on) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    prof_collect(c);
+    if (on) { for (int k = 0; k < P_COUNT; ++k) { c->prof_ms[k] = 0; c->prof_n[k] = 0; } }
+    c->prof_on = on != 0;
+    return FC_OK;
+}
+
+int cache_profile_count(void) { return P_COUNT; }
+
+const char* cache_profile_name(int32_t k) { return (k >= 0 && k < P_COUNT) ? kProfNames[k] : ""; }
+
+int cache_profile_get(fc_cache* c, int32_t k, double* total_ms, int64_t* launches) {
+    if (!c || k < 0 || k >= P_COUNT) return FC_ERR_INVALID_ARG;
+    prof_collect(c);
+    if (total_ms) *total_ms = c->prof_ms[k];
+    if (launches) *launches = c->prof_n[k];
+    return FC_OK;
+}
+
+}  // extern "C"

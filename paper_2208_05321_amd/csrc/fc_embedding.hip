@@ -1,0 +1,415 @@
+// EmbeddingBag-sum forward and the fused backward + SGD step on the cached weight
+// (paper Section 4.3: after the cache step the embedding op and the optimizer run on the cached rows;
+//  Section 2.2: the update is synchronous).
+//
+// Forward: one row-group of lanes per bag, rows added in position order.
+// Backward: lookups are stably radix-sorted by slot (payload = bag index), so each slot's gradients form
+// one contiguous, position-ordered run; fixed chunks of BWD_CHUNK consecutive sorted lookups are reduced by
+// one row-group each (perfectly balanced however skewed the ids are), runs that cross chunk borders are
+// finished by a second small kernel in chunk order.  No floating-point atomics: results are reproducible.
+#include "fc_internal.h"
+
+namespace fc {
+
+template <int VEC> struct Vec;
+template <> struct Vec<1> { using T = float; };
+template <> struct Vec<2> { using T = float2; };
+template <> struct Vec<4> { using T = float4; };
+
+__device__ __forceinline__ float vzero(float) { return 0.f; }
+__device__ __forceinline__ float2 vzero(float2) { return make_float2(0.f, 0.f); }
+__device__ __forceinline__ float4 vzero(float4) { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ float vadd(float a, float b) { return a + b; }
+__device__ __forceinline__ float2 vadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float4 vadd(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+// row - lr * g with the product rounded before the subtraction (no fused multiply-add)
+__device__ __forceinline__ float sgd1(float w, float g, float lr) { return __fsub_rn(w, __fmul_rn(lr, g)); }
+__device__ __forceinline__ float vsgd(float w, float g, float lr) { return sgd1(w, g, lr); }
+__device__ __forceinline__ float2 vsgd(float2 w, float2 g, float lr) { return make_float2(sgd1(w.x, g.x, lr), sgd1(w.y, g.y, lr)); }
+__device__ __forceinline__ float4 vsgd(float4 w, float4 g, float lr) {
+    return make_float4(sgd1(w.x, g.x, lr), sgd1(w.y, g.y, lr), sgd1(w.z, g.z, lr), sgd1(w.w, g.w, lr));
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------------------------------------
+template <int VEC>
+__global__ __launch_bounds__(256) void k_bag_fwd(const float* __restrict__ cache, const int32_t* __restrict__ slots,
+                                                 const int64_t* __restrict__ offsets, int num_bags, int n, int C, int D,
+                                                 int lpr_shift, float* __restrict__ out, Ctl* ctl) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    bool bad = false;
+    for (int b = blockIdx.x * gpb + gl; b < num_bags; b += gridDim.x * gpb) {
+        int64_t beg = offsets[b], end = offsets[b + 1];
+        if (beg < 0) beg = 0;
+        if (end > n) end = n;
+        V* __restrict__ o = reinterpret_cast<V*>(out + (size_t)b * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) {
+            V acc = vzero(V());
+            int64_t i = beg;
+            for (; i + 4 <= end; i += 4) {
+                const int s0 = slots[i], s1 = slots[i + 1], s2 = slots[i + 2], s3 = slots[i + 3];
+                const bool k0 = (unsigned)s0 < (unsigned)C, k1 = (unsigned)s1 < (unsigned)C,
+                           k2 = (unsigned)s2 < (unsigned)C, k3 = (unsigned)s3 < (unsigned)C;
+                bad |= !(k0 && k1 && k2 && k3);
+                const V v0 = k0 ? reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx] : vzero(V());
+                const V v1 = k1 ? reinterpret_cast<const V*>(cache + (size_t)s1 * D)[cidx] : vzero(V());
+                const V v2 = k2 ? reinterpret_cast<const V*>(cache + (size_t)s2 * D)[cidx] : vzero(V());
+                const V v3 = k3 ? reinterpret_cast<const V*>(cache + (size_t)s3 * D)[cidx] : vzero(V());
+                acc = vadd(acc, v0); acc = vadd(acc, v1); acc = vadd(acc, v2); acc = vadd(acc, v3);
+            }
+            for (; i < end; ++i) {
+                const int s0 = slots[i];
+                const bool k0 = (unsigned)s0 < (unsigned)C;
+                bad |= !k0;
+                if (k0) acc = vadd(acc, reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx]);
+            }
+            o[cidx] = acc;
+        }
+    }
+    if (bad) atomicOr(&ctl->async_flags, EF_BAD_SLOT);
+}
+
+static inline int shift_of(int lpr) { int s = 0; while ((1 << s) < lpr) ++s; return s; }
+
+int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && !slots) || (num_bags > 0 && !out))
+        return FC_ERR_INVALID_ARG;
+    if (num_bags == 0) return FC_OK;
+    FC_HIP(hipSetDevice(c->device));
+    const int sh = shift_of(c->lpr);
+    const int gpb = 256 >> sh;
+    int64_t blocks = cdiv(num_bags, gpb);
+    if (blocks > (1 << 20)) blocks = 1 << 20;
+    ProfScope ps(c, P_BAG_FWD, c->stream);
+    switch (c->vec) {
+        case 4: k_bag_fwd<4><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
+        case 2: k_bag_fwd<2><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
+        default: k_bag_fwd<1><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// backward, step 1: stable LSD radix sort of (slot, bag) by slot
+// ---------------------------------------------------------------------------------------------------------
+// First-pass key of lookup i: its slot, or the sentinel C if the slot is out of range.
+__device__ __forceinline__ int first_key(const int32_t* __restrict__ slots, int i, int C, bool& bad) {
+    const int k = slots[i];
+    if ((unsigned)k >= (unsigned)C) { bad = true; return C; }
+    return k;
+}
+
+// bag of lookup i: the largest b with offsets[b] <= i
+__device__ __forceinline__ int bag_of(const int64_t* __restrict__ offsets, int num_bags, int i) {
+    if (i < num_bags && offsets[i] == i && offsets[i + 1] == (int64_t)i + 1) return i;   // one id per bag
+    int lo = 0, hi = num_bags;
+    while (hi - lo > 1) {
+        const int mid = (int)(((int64_t)lo + hi) >> 1);
+        if (offsets[mid] <= i) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restrict__ keys_in, int n, int C, int shift,
+                                                          int radix_bits, int nblk, int32_t* __restrict__ ghist,
+                                                          Ctl* ctl, int first_pass) {
+    __shared__ int h[1 << RS_MAX_BITS];
+    const int radix = 1 << radix_bits, mask = radix - 1;
+    for (int d = threadIdx.x; d < radix; d += RS_THREADS) h[d] = 0;
+    __syncthreads();
+    const int tile0 = blockIdx.x * RS_TILE;
+    bool bad = false;
+#pragma unroll 4
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const int i = tile0 + it * RS_THREADS + threadIdx.x;
+        if (i < n) {
+            const int k = first_pass ? first_key(keys_in, i, C, bad) : keys_in[i];
+            atomicAdd(&h[(k >> shift) & mask], 1);
+        }
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)d * nblk + blockIdx.x] = h[d];
+    if (bad) atomicOr(&ctl->async_flags, EF_BAD_SLOT);
+}
+
+// One wavefront per digit: exclusive scan of that digit's counts over the tiles; the digit total goes to dtot.
+__global__ __launch_bounds__(256) void k_sort_scan(int32_t* ghist, int nblk, int radix, int32_t* __restrict__ dtot) {
+    const int d = (blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (d >= radix) return;
+    int carry = 0;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+        const int b = b0 + lane;
+        const int v = b < nblk ? ghist[(size_t)d * nblk + b] : 0;
+        int x = v;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            int y = __shfl_up(x, o);
+            if (lane >= o) x += y;
+        }
+        if (b < nblk) ghist[(size_t)d * nblk + b] = carry + x - v;
+        carry += __shfl(x, 63);
+    }
+    if (lane == 0) dtot[d] = carry;
+}
+
+__global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __restrict__ keys_in,
+                                                             const int32_t* __restrict__ vals_in,
+                                                             const int64_t* __restrict__ offsets, int num_bags, int n,
+                                                             int C, int shift, int radix_bits, int nblk,
+                                                             const int32_t* __restrict__ ghist,
+                                                             const int32_t* __restrict__ dtot,
+                                                             int32_t* __restrict__ keys_out,
+                                                             int32_t* __restrict__ vals_out, int first_pass) {
+    constexpr int NW = RS_THREADS / 64;
+    __shared__ int base[1 << RS_MAX_BITS];     // where this tile's run of each digit starts in the output
+    __shared__ int wc[NW][1 << RS_MAX_BITS];   // per-wavefront digit counts, then exclusive offsets
+    __shared__ int lds[NW];
+    const int radix = 1 << radix_bits, mask = radix - 1;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    {   // digit bases: exclusive scan of the digit totals, plus this tile's offset within the digit
+        const int per = (radix + RS_THREADS - 1) / RS_THREADS;
+        const int d0 = tid * per;
+        int local = 0;
+        for (int k = 0; k < per; ++k) if (d0 + k < radix) local += dtot[d0 + k];
+        int tot;
+        int run = block_excl_scan<RS_THREADS>(local, tot, lds);
+        for (int k = 0; k < per; ++k) {
+            const int d = d0 + k;
+            if (d < radix) {
+                base[d] = run + ghist[(size_t)d * nblk + blockIdx.x];
+                run += dtot[d];
+            }
+        }
+        for (int d = tid; d < radix; d += RS_THREADS) {
+#pragma unroll
+            for (int k = 0; k < NW; ++k) wc[k][d] = 0;
+        }
+    }
+    __syncthreads();
+    const int tile0 = blockIdx.x * RS_TILE + w * (RS_TILE / NW);
+    const uint64_t lt = (1ull << lane) - 1ull;
+    int key[RS_ITEMS], val[RS_ITEMS], lrank[RS_ITEMS];
+    bool bad = false;
+#pragma unroll
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const int i = tile0 + it * 64 + lane;
+        const bool valid = i < n;
+        int k = 0, v = 0;
+        if (valid) {
+            if (first_pass) { k = first_key(keys_in, i, C, bad); v = bag_of(offsets, num_bags, i); }
+            else { k = keys_in[i]; v = vals_in[i]; }
+        }
+        const int d = (k >> shift) & mask;
+        uint64_t peers = __ballot(valid);
+        for (int b = 0; b < radix_bits; ++b) {
+            const bool one = (d >> b) & 1;
+            const uint64_t bm = __ballot(one);
+            peers &= one ? bm : ~bm;
+        }
+        const int before = __popcll(peers & lt);
+        int old = 0;
+        if (valid) old = wc[w][d];
+        if (valid && before == 0) wc[w][d] = old + __popcll(peers);
+        lrank[it] = old + before;
+        key[it] = k;
+        val[it] = v;
+    }
+    __syncthreads();
+    for (int d = tid; d < radix; d += RS_THREADS) {
+        int run = 0;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) { const int cnt = wc[k][d]; wc[k][d] = run; run += cnt; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < RS_ITEMS; ++it) {
+        const int i = tile0 + it * 64 + lane;
+        if (i < n) {
+            const int d = (key[it] >> shift) & mask;
+            const int dest = base[d] + wc[w][d] + lrank[it];
+            keys_out[dest] = key[it];
+            vals_out[dest] = val[it];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// backward, step 2: chunked segmented reduction + SGD
+// ---------------------------------------------------------------------------------------------------------
+// pmeta[g] = {kind of the chunk's first run (0 complete / none pending, 1 = ends a run begun earlier,
+//             2 = whole chunk inside a longer run), 1 if the chunk's last run continues, slot of that run, 0}
+template <int VEC>
+__global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ keys, const int32_t* __restrict__ vals,
+                                                    int n, int C, const float* __restrict__ grad, float* cache, int D,
+                                                    int lpr_shift, float lr, float* __restrict__ part,
+                                                    int32_t* __restrict__ pmeta) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    const int64_t g = (int64_t)blockIdx.x * gpb + gl;
+    const int64_t beg = g * BWD_CHUNK;
+    if (beg >= n) return;
+    const int end = (int)(beg + BWD_CHUNK < n ? beg + BWD_CHUNK : n);
+    V* __restrict__ pfirst = reinterpret_cast<V*>(part + (size_t)(g * 2) * D);
+    V* __restrict__ plast = reinterpret_cast<V*>(part + (size_t)(g * 2 + 1) * D);
+    int first_kind = 0, has_head = 0, head_slot = -1;
+    for (int cidx = lane; cidx < nv; cidx += lpr) {
+        int cur = keys[beg];
+        bool open_left = beg > 0 && keys[beg - 1] == cur;
+        first_kind = 0; has_head = 0; head_slot = -1;
+        V acc = vzero(V());
+        for (int e = (int)beg; e < end; ++e) {
+            const int k = keys[e];
+            if (k != cur) {                       // run of `cur` ends inside the chunk
+                if (open_left) { pfirst[cidx] = acc; first_kind = 1; }
+                else if (cur < C) {
+                    V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
+                    row[cidx] = vsgd(row[cidx], acc, lr);
+                }
+                open_left = false;
+                cur = k;
+                acc = vzero(V());
+            }
+            acc = vadd(acc, reinterpret_cast<const V*>(grad + (size_t)vals[e] * D)[cidx]);
+        }
+        const bool open_right = end < n && keys[end] == cur;
+        if (open_left) { pfirst[cidx] = acc; first_kind = open_right ? 2 : 1; }
+        else if (open_right) { plast[cidx] = acc; has_head = 1; head_slot = cur; }
+        else if (cur < C) {
+            V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
+            row[cidx] = vsgd(row[cidx], acc, lr);
+        }
+    }
+    if (lane == 0) {
+        pmeta[g * 4 + 0] = first_kind;
+        pmeta[g * 4 + 1] = has_head;
+        pmeta[g * 4 + 2] = head_slot;
+    }
+}
+
+// Runs that cross chunk borders: the chunk where the run starts adds the later chunks' pieces in order.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_bwd_fixup(int n, int C, float* cache, int D, int lpr_shift, float lr,
+                                                   const float* __restrict__ part, const int32_t* __restrict__ pmeta,
+                                                   int64_t groups) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    const int64_t g = (int64_t)blockIdx.x * gpb + gl;
+    if (g >= groups || !pmeta[g * 4 + 1]) return;
+    const int slot = pmeta[g * 4 + 2];
+    if (slot >= C) return;
+    for (int cidx = lane; cidx < nv; cidx += lpr) {
+        V acc = reinterpret_cast<const V*>(part + (size_t)(g * 2 + 1) * D)[cidx];
+        for (int64_t h = g + 1; h < groups; ++h) {
+            acc = vadd(acc, reinterpret_cast<const V*>(part + (size_t)(h * 2) * D)[cidx]);
+            if (pmeta[h * 4] != 2) break;
+        }
+        V* row = reinterpret_cast<V*>(cache + (size_t)slot * D);
+        row[cidx] = vsgd(row[cidx], acc, lr);
+    }
+}
+
+static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
+    if (n > c->sort_cap) {
+        FC_HIP(hipStreamSynchronize(c->stream));
+        for (int32_t** p : {&c->keysA, &c->valsA, &c->keysB, &c->valsB}) { if (*p) FC_HIP(hipFree(*p)); *p = nullptr; }
+        c->sort_cap = 0;
+        const int64_t cap = n + n / 4 + 1024;
+        for (int32_t** p : {&c->keysA, &c->valsA, &c->keysB, &c->valsB}) FC_HIP(hipMalloc((void**)p, (size_t)cap * 4));
+        c->sort_cap = cap;
+    }
+    const int64_t gh = nblk << RS_MAX_BITS;
+    if (gh > c->ghist_cap) {
+        FC_HIP(hipStreamSynchronize(c->stream));
+        if (c->ghist) FC_HIP(hipFree(c->ghist));
+        c->ghist = nullptr; c->ghist_cap = 0;
+        FC_HIP(hipMalloc((void**)&c->ghist, (size_t)(gh + gh / 4) * 4));
+        c->ghist_cap = gh + gh / 4;
+    }
+    if (!c->dtot) FC_HIP(hipMalloc((void**)&c->dtot, (size_t)(1 << RS_MAX_BITS) * 4));
+    if (groups > c->part_groups) {
+        FC_HIP(hipStreamSynchronize(c->stream));
+        if (c->part) FC_HIP(hipFree(c->part));
+        if (c->pmeta) FC_HIP(hipFree(c->pmeta));
+        c->part = nullptr; c->pmeta = nullptr; c->part_groups = 0;
+        const int64_t cap = groups + groups / 4 + 64;
+        FC_HIP(hipMalloc((void**)&c->part, (size_t)cap * 2 * c->D * 4));
+        FC_HIP(hipMalloc((void**)&c->pmeta, (size_t)cap * 4 * 4));
+        c->part_groups = cap;
+    }
+    return FC_OK;
+}
+
+int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+             const float* grad, float lr) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!slots || !grad || num_bags == 0)))
+        return FC_ERR_INVALID_ARG;
+    if (n == 0) return FC_OK;
+    FC_HIP(hipSetDevice(c->device));
+    hipStream_t st = c->stream;
+    int bits = 1;
+    while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
+    const int passes = (bits + RS_MAX_BITS - 1) / RS_MAX_BITS;
+    const int rb = (bits + passes - 1) / passes;
+    const int radix = 1 << rb;
+    const int64_t nblk = cdiv(n, RS_TILE);
+    const int64_t groups = cdiv(n, BWD_CHUNK);
+    FC_TRY(ensure_bwd(c, n, nblk, groups));
+    const int32_t* kin = slots; const int32_t* vin = nullptr;
+    int32_t* kout = c->keysA; int32_t* vout = c->valsA;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = p * rb;
+        {
+            ProfScope ps(c, P_SORT_HIST, st);
+            k_sort_hist<<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, (int)n, (int)c->C, shift, rb, (int)nblk, c->ghist, c->ctl, p == 0);
+        }
+        {
+            ProfScope ps(c, P_SORT_SCAN, st);
+            k_sort_scan<<<(unsigned)cdiv((int64_t)radix * 64, 256), 256, 0, st>>>(c->ghist, (int)nblk, radix, c->dtot);
+        }
+        {
+            ProfScope ps(c, P_SORT_SCATTER, st);
+            k_sort_scatter<<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, vin, offsets, (int)num_bags, (int)n, (int)c->C, shift, rb,
+                                                                 (int)nblk, c->ghist, c->dtot, kout, vout, p == 0);
+        }
+        kin = kout; vin = vout;
+        if (kout == c->keysA) { kout = c->keysB; vout = c->valsB; } else { kout = c->keysA; vout = c->valsA; }
+    }
+    const int sh = shift_of(c->lpr);
+    const int gpb = 256 >> sh;
+    const unsigned blocks = (unsigned)cdiv(groups, gpb);
+    {
+        ProfScope ps(c, P_BWD_REDUCE, st);
+        switch (c->vec) {
+            case 4: k_bwd_reduce<4><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
+            case 2: k_bwd_reduce<2><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
+            default: k_bwd_reduce<1><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
+        }
+    }
+    {
+        ProfScope ps(c, P_BWD_FIXUP, st);
+        switch (c->vec) {
+            case 4: k_bwd_fixup<4><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
+            case 2: k_bwd_fixup<2><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
+            default: k_bwd_fixup<1><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
+        }
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+}  // namespace fc

@@ -1,0 +1,188 @@
+// Internal declarations shared by the freqcache HIP sources (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/freqcache.h"
+
+namespace fc {
+
+constexpr int WAVE = 64;
+// Rank-space bitmaps are scanned in tiles of RT_WORDS 32-bit words (one workgroup each):
+// 256 threads x one uint4, i.e. 32768 ranks per tile.
+constexpr int RT_THREADS = 256;
+constexpr int RT_WORDS = RT_THREADS * 4;
+// Radix sort of (slot, bag) pairs for the backward pass.
+constexpr int RS_THREADS = 256;
+constexpr int RS_ITEMS = 16;
+constexpr int RS_TILE = RS_THREADS * RS_ITEMS;
+constexpr int RS_MAX_BITS = 11;
+// Consecutive sorted lookups reduced by one row-group in the backward pass.
+constexpr int BWD_CHUNK = 32;
+
+// Sticky device-side flags.
+enum : uint32_t { EF_BAD_OFFSETS = 1u, EF_ID_RANGE = 2u, EF_BAD_SLOT = 4u };
+
+// Device-resident control block, read and written by the planning kernels.
+struct Ctl {
+    uint32_t err_flags;     // EF_* raised by the current cache_prepare
+    uint32_t async_flags;   // EF_BAD_SLOT raised by fwd / bwd kernels
+    int32_t hit_ids;        // ids whose row was resident before this batch
+    int32_t nfree;          // empty slots
+    int32_t status;         // FC_* decision of the current cache_prepare
+    int32_t n_unique, n_miss, need;
+};
+
+// Host-visible (pinned, mapped) copy of the decision, written by the planning kernel.
+struct HostCtl {
+    int32_t status, n_unique, n_miss, need, hit_ids, nfree, async_flags, pad;
+};
+
+enum ProfItem {
+    P_REMAP_MARK = 0, P_RANK_COUNT, P_RANK_PLAN, P_RANK_EMIT, P_EVICT_GATHER, P_EVICT_STORE, P_FREE_PICK,
+    P_MISS_FILL, P_SLOTS_OUT, P_BAG_FWD, P_SORT_HIST, P_SORT_SCAN, P_SORT_SCATTER, P_BWD_REDUCE, P_BWD_FIXUP,
+    P_H2D_BLOCK, P_D2H_BLOCK, P_FLUSH_ROWS, P_COUNT
+};
+
+struct ProfSpan { int item; hipEvent_t a, b; };
+
+}  // namespace fc
+
+struct fc_cache {
+    int64_t N = 0, C = 0;
+    int32_t D = 0;
+    int64_t staging_rows = 0;
+    int32_t flags = 0;
+    int device = 0;
+    hipStream_t stream = nullptr, side = nullptr;
+    hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
+    bool evict_pending = false;
+
+    // row geometry: VEC floats per lane access, LPR lanes per row
+    int vec = 1, lpr = 1;
+
+    // device state
+    int32_t* freq_rank = nullptr;   // [N]  idx_map
+    int32_t* rank_slot = nullptr;   // [N]  cpu_row_idx -> gpu_row_idx, -1 = not resident
+    int32_t* slot_rank = nullptr;   // [C]  gpu_row_idx -> cpu_row_idx, -1 = empty
+    float* cache = nullptr;         // [C][D]
+    uint32_t* ubits = nullptr;      // rank-space bitmap: rows used by the current batch (zero between calls)
+    uint32_t* rbits = nullptr;      // rank-space bitmap: resident rows
+    uint32_t* fbits = nullptr;      // slot-space bitmap: empty slots
+    int64_t NB = 0;                 // rank-space tiles
+    int64_t CW = 0;                 // words of fbits (padded to 1024)
+    int32_t* bsum = nullptr;        // [3][NB] per-tile counts: used, missing, evictable
+    int32_t* moff = nullptr;        // [NB] output offset of a tile's missing ranks
+    int32_t* vtake = nullptr;       // [NB] victims taken from a tile
+    int32_t* voff = nullptr;        // [NB] output offset of a tile's victims
+    int32_t* miss_ranks = nullptr;  // [C]
+    int32_t* vrank = nullptr;       // [C]
+    int32_t* vslot = nullptr;       // [C]
+    int32_t* fill_slots = nullptr;  // [C]
+    int32_t* rbuf = nullptr;        // [n_cap] rank of every input id
+    int64_t n_cap = 0;
+    fc::Ctl* ctl = nullptr;
+    fc::HostCtl* hctl = nullptr;    // pinned
+    float* stage_dev = nullptr;     // [staging_rows][D] evicted-row block
+    float* stage_dev2 = nullptr;    // staged mode: H2D block
+    float* stage_pin = nullptr;     // staged mode: pinned block (both directions)
+    int32_t* list_pin = nullptr;    // staged mode: pinned copies of miss / victim rank lists [2*C]
+
+    float* host = nullptr;          // pinned, rank-ordered table
+    float* host_dev = nullptr;      // its device-side address
+    bool own_host = false;
+
+    // backward-pass scratch
+    int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;
+    int32_t *ghist = nullptr, *dtot = nullptr;
+    int64_t sort_cap = 0, ghist_cap = 0;
+    float* part = nullptr;          // [groups][2][D] partial sums of slots spanning chunk borders
+    int32_t* pmeta = nullptr;       // [groups][4]
+    int64_t part_groups = 0;
+
+    // last prepare
+    fc_stats last = {};
+    bool have_lists = false;
+
+    // profiling
+    bool prof_on = false;
+    std::vector<fc::ProfSpan> spans;
+    std::vector<hipEvent_t> ev_pool;
+    double prof_ms[fc::P_COUNT] = {};
+    int64_t prof_n[fc::P_COUNT] = {};
+};
+
+namespace fc {
+
+// ---- error plumbing ----
+#define FC_HIP(expr)                                   \
+    do {                                               \
+        hipError_t _e = (expr);                        \
+        if (_e != hipSuccess) {                        \
+            (void)hipGetLastError();                   \
+            return (_e == hipErrorOutOfMemory) ? FC_ERR_OOM_DEVICE : FC_ERR_HIP; \
+        }                                              \
+    } while (0)
+
+#define FC_TRY(expr)                  \
+    do {                              \
+        int _rc = (expr);             \
+        if (_rc != FC_OK) return _rc; \
+    } while (0)
+
+// Optional event bracket around one launch / copy on stream `s`.
+struct ProfScope {
+    fc_cache* c; hipStream_t s; int item; hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(fc_cache* c_, int item_, hipStream_t s_);
+    ~ProfScope();
+};
+void prof_collect(fc_cache* c);
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// entry points implemented across the sources
+int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots);
+int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
+int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+             const float* grad, float lr);
+
+// row movement (fc_rows.hip).  dst_idx / src_idx: per-row index lists in device memory, or nullptr for row j.
+// dst_rows / src_rows bound the row indices on either side (rows with an index outside are skipped).
+int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, const int32_t* dst_idx, int64_t dst_rows,
+                     const float* src, const int32_t* src_idx, int64_t src_rows, int64_t rows, int max_blocks);
+// host[slot_rank[s]] = cache[s] for every resident slot, written straight into the mapped host table.
+int launch_flush_rows(fc_cache* c, hipStream_t s);
+
+// ---- device helpers ----
+template <int NT>
+__device__ __forceinline__ int block_excl_scan(int v, int& total, int* lds /* NT/64 ints */) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int y = __shfl_up(x, o);
+        if (lane >= o) x += y;
+    }
+    if (lane == 63) lds[w] = x;
+    __syncthreads();
+    int wbase = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) {
+        int s = lds[i];
+        if (i < w) wbase += s;
+        tot += s;
+    }
+    __syncthreads();
+    total = tot;
+    return wbase + x - v;
+}
+
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_down(x, o);
+    return x;  // valid in lane 0
+}
+
+}  // namespace fc

@@ -1,0 +1,410 @@
+// cache_prepare: Algorithm 1 of the paper (PrepareCache + PrepareCPURowIdxOnGPU, Section 4.3) as a short
+// chain of gfx950 kernels.
+//
+// The paper's prototype strings together framework calls (unique, isin, nonzero, index_fill, argsort,
+// index_copy).  Here the same decisions come out of three bitmaps and popcount scans, with no sort:
+//   ubits  rank space, rows used by this batch        -> unique() is "which bits are set", ascending for free
+//   rbits  rank space, rows resident in HBM           -> missing = ubits & ~rbits, evictable = rbits & ~ubits
+//   fbits  slot space, empty slots                    -> the i-th missing rank takes the i-th set bit
+// "The evict_num largest cpu_row_idx not used by the batch" (LFU by static frequency rank) is the top
+// evict_num set bits of (rbits & ~ubits): a suffix count over bitmap tiles finds the threshold tile.
+#include "fc_internal.h"
+
+#include <omp.h>
+#include <string.h>
+
+namespace fc {
+
+// ---------------------------------------------------------------------------------------------------------
+// K1  ids -> frequency rank (idx_map lookup), mark the rank in ubits, count access-level hits, check offsets.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_remap_mark(const int64_t* __restrict__ ids, int n,
+                                                    const int64_t* __restrict__ offsets, int num_bags,
+                                                    const int32_t* __restrict__ freq_rank, int64_t N, uint32_t* ubits,
+                                                    const uint32_t* __restrict__ rbits, int32_t* __restrict__ rbuf,
+                                                    Ctl* ctl) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    bool hit = false;
+    uint32_t flags = 0;
+    if (i < n) {
+        const int64_t id = ids[i];
+        int r = -1;
+        if (id < 0 || id >= N) {
+            flags |= EF_ID_RANGE;
+        } else {
+            r = freq_rank[id];
+            const uint32_t w = (uint32_t)r >> 5, bit = 1u << (r & 31);
+            // Bits are only ever set during this kernel, so a plain read that already sees the bit is
+            // final; hot rows then cost one read instead of thousands of same-address atomics.
+            if (!(ubits[w] & bit)) atomicOr(&ubits[w], bit);
+            hit = (rbits[w] & bit) != 0;
+        }
+        rbuf[i] = r;
+    }
+    if (i <= num_bags) {
+        const int64_t o = offsets[i];
+        if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
+        if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
+        if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
+    }
+    const uint64_t hb = __ballot(hit);
+    if ((threadIdx.x & 63) == 0 && hb) atomicAdd(&ctl->hit_ids, __popcll(hb));
+    if (flags) atomicOr(&ctl->err_flags, flags);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K2a  per rank-space tile: rows used, rows missing, rows evictable.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restrict__ ubits4,
+                                                           const uint4* __restrict__ rbits4,
+                                                           int32_t* __restrict__ bsum, int NB) {
+    __shared__ int lds[3][RT_THREADS / 64];
+    const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
+    const uint4 u = ubits4[idx], r = rbits4[idx];
+    int cu = __popc(u.x) + __popc(u.y) + __popc(u.z) + __popc(u.w);
+    int cm = __popc(u.x & ~r.x) + __popc(u.y & ~r.y) + __popc(u.z & ~r.z) + __popc(u.w & ~r.w);
+    int cc = __popc(r.x & ~u.x) + __popc(r.y & ~u.y) + __popc(r.z & ~u.z) + __popc(r.w & ~u.w);
+    cu = wave_sum(cu); cm = wave_sum(cm); cc = wave_sum(cc);
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    if (lane == 0) { lds[0][w] = cu; lds[1][w] = cm; lds[2][w] = cc; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < RT_THREADS / 64; ++k) s += lds[threadIdx.x][k];
+        bsum[(size_t)threadIdx.x * NB + blockIdx.x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K2b  one workgroup: totals, the call's status, evict_num = numel(miss) - empty slots, output offsets of
+//      every tile's missing ranks, and which tiles give up how many victims (from the top rank down).
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
+                                                    HostCtl* hctl, int32_t* __restrict__ moff,
+                                                    int32_t* __restrict__ vtake, int32_t* __restrict__ voff) {
+    __shared__ int lds[16];
+    const int tid = threadIdx.x;
+    int carryM = 0, totU = 0;
+    for (int base = 0; base < NB; base += 1024) {
+        const int b = base + tid;
+        const int m = b < NB ? bsum[(size_t)NB + b] : 0;
+        const int u = b < NB ? bsum[b] : 0;
+        int tot, totu;
+        const int ex = block_excl_scan<1024>(m, tot, lds);
+        if (b < NB) moff[b] = carryM + ex;
+        carryM += tot;
+        (void)block_excl_scan<1024>(u, totu, lds);
+        totU += totu;
+    }
+    const uint32_t ef = ctl->err_flags;
+    const int nfree = ctl->nfree;
+    int status = FC_OK;
+    if (ef & EF_BAD_OFFSETS) status = FC_ERR_BAD_OFFSETS;
+    else if (ef & EF_ID_RANGE) status = FC_ERR_ID_OUT_OF_RANGE;
+    else if (totU > C) status = FC_ERR_BATCH_EXCEEDS_CACHE;
+    const int M = carryM;
+    int need = M - nfree;
+    if (need < 0 || status != FC_OK) need = 0;
+    // Victims: walk tiles from the highest ranks down; `above` = evictable rows in tiles of larger rank.
+    int carry = 0;
+    for (int base = 0; base < NB; base += 1024) {
+        const int b = NB - 1 - (base + tid);
+        const int cc = b >= 0 ? bsum[(size_t)2 * NB + b] : 0;
+        int tot;
+        const int above = carry + block_excl_scan<1024>(cc, tot, lds);
+        if (b >= 0) {
+            int take = 0, off = 0;
+            if (above < need && cc > 0) {
+                take = min(cc, need - above);
+                off = need - above - take;   // victims are listed in ascending rank
+            }
+            vtake[b] = take;
+            voff[b] = off;
+        }
+        carry += tot;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const int hits = ctl->hit_ids;
+        ctl->status = status;
+        ctl->n_unique = totU;
+        ctl->n_miss = M;
+        ctl->need = need;
+        const int nf = status == FC_OK ? nfree + need - M : nfree;
+        ctl->nfree = nf;
+        ctl->err_flags = 0;
+        ctl->hit_ids = 0;
+        hctl->status = status; hctl->n_unique = totU; hctl->n_miss = M; hctl->need = need;
+        hctl->hit_ids = hits; hctl->nfree = nf; hctl->async_flags = (int32_t)ctl->async_flags;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K2c  per tile: write the missing ranks (ascending), pick and retire the victims, update rbits, clear ubits.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* rbits4, const Ctl* __restrict__ ctl,
+                                                          const int32_t* __restrict__ moff,
+                                                          const int32_t* __restrict__ vtake,
+                                                          const int32_t* __restrict__ voff,
+                                                          int32_t* __restrict__ miss_ranks, int32_t* __restrict__ vrank,
+                                                          int32_t* __restrict__ vslot, int32_t* rank_slot,
+                                                          int32_t* slot_rank, uint32_t* fbits, int C) {
+    __shared__ int lds[RT_THREADS / 64];
+    const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
+    const uint4 u4 = ubits4[idx];
+    const bool anyu = (u4.x | u4.y | u4.z | u4.w) != 0;
+    if (ctl->status != FC_OK) {            // failed call: forget the marks, touch nothing else
+        if (anyu) ubits4[idx] = make_uint4(0, 0, 0, 0);
+        return;
+    }
+    const uint4 r4 = rbits4[idx];
+    const uint32_t uw[4] = {u4.x, u4.y, u4.z, u4.w};
+    const uint32_t rw[4] = {r4.x, r4.y, r4.z, r4.w};
+    uint32_t mw[4], cw[4], vw[4] = {0, 0, 0, 0};
+    int cm = 0, cc = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        mw[k] = uw[k] & ~rw[k];
+        cw[k] = rw[k] & ~uw[k];
+        cm += __popc(mw[k]);
+        cc += __popc(cw[k]);
+    }
+    const int rank0 = (int)(idx * 128);
+    int totm;
+    const int pm = block_excl_scan<RT_THREADS>(cm, totm, lds);
+    if (cm) {
+        int o = moff[blockIdx.x] + pm;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t word = mw[k];
+            while (word) {
+                const int bit = __ffs(word) - 1;
+                miss_ranks[o++] = rank0 + k * 32 + bit;
+                word &= word - 1;
+            }
+        }
+    }
+    const int vt = vtake[blockIdx.x];
+    if (vt > 0) {
+        int totc;
+        const int pc = block_excl_scan<RT_THREADS>(cc, totc, lds);
+        const int skip = totc - vt;          // the lowest `skip` evictable ranks of the threshold tile stay
+        const int o0 = voff[blockIdx.x];
+        int q = pc;
+        if (cc && pc + cc > skip) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t word = cw[k];
+                while (word) {
+                    const int bit = __ffs(word) - 1;
+                    if (q >= skip) {
+                        const int rank = rank0 + k * 32 + bit;
+                        const int slot = rank_slot[rank];
+                        const int j = o0 + q - skip;
+                        vrank[j] = rank;
+                        vslot[j] = slot;
+                        rank_slot[rank] = -1;
+                        if ((unsigned)slot < (unsigned)C) {   // always true while the two maps are inverse
+                            slot_rank[slot] = -1;
+                            atomicOr(&fbits[slot >> 5], 1u << (slot & 31));
+                        }
+                        vw[k] |= 1u << bit;
+                    }
+                    ++q;
+                    word &= word - 1;
+                }
+            }
+        }
+    }
+    if (cm || (vw[0] | vw[1] | vw[2] | vw[3]))
+        rbits4[idx] = make_uint4((rw[0] & ~vw[0]) | mw[0], (rw[1] & ~vw[1]) | mw[1], (rw[2] & ~vw[2]) | mw[2],
+                                 (rw[3] & ~vw[3]) | mw[3]);
+    if (anyu) ubits4[idx] = make_uint4(0, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K6  the i-th missing rank takes the i-th lowest empty slot; both index maps are updated.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void k_free_pick(uint32_t* fbits, int CW, int M,
+                                                    const int32_t* __restrict__ miss_ranks,
+                                                    int32_t* __restrict__ fill_slots, int32_t* slot_rank,
+                                                    int32_t* rank_slot) {
+    __shared__ int lds[16];
+    const int tid = threadIdx.x;
+    int base = 0;
+    for (int w0 = 0; w0 < CW && base < M; w0 += 1024) {
+        const int w = w0 + tid;
+        uint32_t word = w < CW ? fbits[w] : 0u;
+        const int cnt = __popc(word);
+        int tot;
+        int j = base + block_excl_scan<1024>(cnt, tot, lds);
+        if (cnt && j < M) {
+            uint32_t keep = word;
+            while (word && j < M) {
+                const int bit = __ffs(word) - 1;
+                const int slot = w * 32 + bit;
+                const int r = miss_ranks[j];
+                fill_slots[j] = slot;
+                slot_rank[slot] = r;
+                rank_slot[r] = slot;
+                keep &= ~(1u << bit);
+                word &= word - 1;
+                ++j;
+            }
+            fbits[w] = keep;
+        }
+        base += tot;
+    }
+}
+
+// K8  gpu_row_idx of every input id.
+__global__ __launch_bounds__(256) void k_slots_out(const int32_t* __restrict__ rbuf,
+                                                   const int32_t* __restrict__ rank_slot, int32_t* __restrict__ slots,
+                                                   int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) slots[i] = rank_slot[rbuf[i]];
+}
+
+// ---------------------------------------------------------------------------------------------------------
+static int ensure_rbuf(fc_cache* c, int64_t n) {
+    if (n <= c->n_cap) return FC_OK;
+    FC_HIP(hipStreamSynchronize(c->stream));
+    if (c->rbuf) FC_HIP(hipFree(c->rbuf));
+    c->rbuf = nullptr; c->n_cap = 0;
+    const int64_t cap = n + n / 4 + 1024;
+    FC_HIP(hipMalloc((void**)&c->rbuf, (size_t)cap * 4));
+    c->n_cap = cap;
+    return FC_OK;
+}
+
+// Evicted rows, default transmitter: gather into a device block on the caller's stream (so the slots can be
+// refilled at once), then store the block into the mapped host table on the side stream, off the critical path.
+static int evict_direct(fc_cache* c, int64_t need) {
+    const int64_t S = c->staging_rows;
+    for (int64_t off = 0; off < need; off += S) {
+        const int64_t rows = need - off < S ? need - off : S;
+        if (off > 0) FC_HIP(hipStreamWaitEvent(c->stream, c->ev_evict_done, 0));   // block buffer is being read
+        FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
+        FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
+        FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->vrank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, 512));
+        FC_HIP(hipEventRecord(c->ev_evict_done, c->side));
+        c->evict_pending = true;
+    }
+    return FC_OK;
+}
+
+// The paper's transmitter: block on the source side -> one bulk copy -> scatter on the target side.
+static int evict_staged(fc_cache* c, int64_t need, const int32_t* vrank_host) {
+    const int64_t S = c->staging_rows;
+    const size_t rowb = (size_t)c->D * 4;
+    for (int64_t off = 0; off < need; off += S) {
+        const int64_t rows = need - off < S ? need - off : S;
+        FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        {
+            ProfScope ps(c, P_D2H_BLOCK, c->stream);
+            FC_HIP(hipMemcpyAsync(c->stage_pin, c->stage_dev, rows * rowb, hipMemcpyDeviceToHost, c->stream));
+        }
+        FC_HIP(hipStreamSynchronize(c->stream));
+        float* host = c->host; const float* blk = c->stage_pin; const int32_t* vr = vrank_host + off;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < rows; ++j) memcpy(host + (size_t)vr[j] * c->D, blk + (size_t)j * c->D, rowb);
+    }
+    return FC_OK;
+}
+
+static int fill_staged(fc_cache* c, int64_t M, const int32_t* miss_host) {
+    const int64_t S = c->staging_rows;
+    const size_t rowb = (size_t)c->D * 4;
+    for (int64_t off = 0; off < M; off += S) {
+        const int64_t rows = M - off < S ? M - off : S;
+        const float* host = c->host; float* blk = c->stage_pin; const int32_t* mr = miss_host + off;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < rows; ++j) memcpy(blk + (size_t)j * c->D, host + (size_t)mr[j] * c->D, rowb);
+        {
+            ProfScope ps(c, P_H2D_BLOCK, c->stream);
+            FC_HIP(hipMemcpyAsync(c->stage_dev2, c->stage_pin, rows * rowb, hipMemcpyHostToDevice, c->stream));
+        }
+        FC_TRY(launch_copy_rows(c, c->stream, P_MISS_FILL, c->cache, c->fill_slots + off, c->C, c->stage_dev2, nullptr, c->staging_rows, rows, 1 << 20));
+        FC_HIP(hipStreamSynchronize(c->stream));   // the pinned block is reused by the next round
+    }
+    return FC_OK;
+}
+
+int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!ids || !slots)))
+        return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_TRY(ensure_rbuf(c, n));
+    hipStream_t st = c->stream;
+    // Last batch's evicted rows must have reached the host table before its block buffer / lists are reused
+    // and before any of those rows could be fetched again.
+    if (c->evict_pending) {
+        FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0));
+        c->evict_pending = false;
+    }
+    const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
+    {
+        ProfScope ps(c, P_REMAP_MARK, st);
+        k_remap_mark<<<(unsigned)cdiv(work, 256), 256, 0, st>>>(ids, (int)n, offsets, (int)num_bags, c->freq_rank, c->N,
+                                                               c->ubits, c->rbits, c->rbuf, c->ctl);
+    }
+    {
+        ProfScope ps(c, P_RANK_COUNT, st);
+        k_rank_count<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((const uint4*)c->ubits, (const uint4*)c->rbits, c->bsum, (int)c->NB);
+    }
+    {
+        ProfScope ps(c, P_RANK_PLAN, st);
+        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff);
+    }
+    FC_HIP(hipEventRecord(c->ev_plan, st));
+    {
+        ProfScope ps(c, P_RANK_EMIT, st);
+        k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, c->ctl, c->moff, c->vtake, c->voff,
+                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, c->fbits, (int)c->C);
+    }
+    FC_HIP(hipGetLastError());
+    FC_HIP(hipEventSynchronize(c->ev_plan));
+    HostCtl h;
+    {
+        const volatile int32_t* hv = reinterpret_cast<const volatile int32_t*>(c->hctl);
+        h.status = hv[0]; h.n_unique = hv[1]; h.n_miss = hv[2]; h.need = hv[3]; h.hit_ids = hv[4]; h.nfree = hv[5];
+        h.async_flags = hv[6]; h.pad = 0;
+    }
+    if (h.status != FC_OK) return h.status;
+    const int64_t M = h.n_miss, need = h.need;
+    const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;
+    if (staged && (M > 0 || need > 0)) {
+        if (M > 0) FC_HIP(hipMemcpyAsync(c->list_pin, c->miss_ranks, (size_t)M * 4, hipMemcpyDeviceToHost, st));
+        if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
+        FC_HIP(hipStreamSynchronize(st));
+    }
+    if (need > 0) FC_TRY(staged ? evict_staged(c, need, c->list_pin + c->C) : evict_direct(c, need));
+    if (M > 0) {
+        {
+            ProfScope ps(c, P_FREE_PICK, st);
+            k_free_pick<<<1, 1024, 0, st>>>(c->fbits, (int)c->CW, (int)M, c->miss_ranks, c->fill_slots, c->slot_rank, c->rank_slot);
+        }
+        if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
+        else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
+    }
+    if (n > 0) {
+        ProfScope ps(c, P_SLOTS_OUT, st);
+        k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
+    }
+    FC_HIP(hipGetLastError());
+    c->last.n_ids = n;
+    c->last.n_unique = h.n_unique;
+    c->last.n_hit_unique = h.n_unique - M;
+    c->last.n_hit_ids = h.hit_ids;
+    c->last.n_miss = M;
+    c->last.n_evict = need;
+    c->last.bytes_h2d = M * (int64_t)c->D * 4;
+    c->last.bytes_d2h = need * (int64_t)c->D * 4;
+    c->have_lists = true;
+    return FC_OK;
+}
+
+}  // namespace fc

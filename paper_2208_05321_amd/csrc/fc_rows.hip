@@ -1,0 +1,87 @@
+// Row movement: one row-group of lanes per embedding row, 16-byte accesses where dim allows.
+// Used for the evict gather, the host-table store of evicted rows, the miss fill and the flush
+// (paper Section 4.3, "data transmitter": rows scattered in one memory become a block in the other).
+#include "fc_internal.h"
+
+namespace fc {
+
+template <int VEC> struct Vec;
+template <> struct Vec<1> { using T = float; };
+template <> struct Vec<2> { using T = float2; };
+template <> struct Vec<4> { using T = float4; };
+
+// dst[dst_idx ? dst_idx[j] : j] = src[src_idx ? src_idx[j] : j] for j in [0, rows); row length D floats.
+// lpr (power of two, <= 64) consecutive lanes own one row; a lane moves VEC floats per access.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_copy_rows(float* __restrict__ dst, const int32_t* __restrict__ dst_idx,
+                                                   unsigned dst_rows, const float* __restrict__ src,
+                                                   const int32_t* __restrict__ src_idx, unsigned src_rows, int rows,
+                                                   int D, int lpr_shift) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    for (int j = blockIdx.x * gpb + gl; j < rows; j += gridDim.x * gpb) {
+        const int di = dst_idx ? dst_idx[j] : j;
+        const int si = src_idx ? src_idx[j] : j;
+        if ((unsigned)di >= dst_rows || (unsigned)si >= src_rows) continue;   // never true for lists this library builds
+        const V* __restrict__ s = reinterpret_cast<const V*>(src + (size_t)si * D);
+        V* __restrict__ d = reinterpret_cast<V*>(dst + (size_t)di * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = s[cidx];
+    }
+}
+
+// Flush: every resident slot's row goes to its place in the host table.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_flush_rows(float* __restrict__ host, const float* __restrict__ cache,
+                                                    const int32_t* __restrict__ slot_rank, int C, int D, int lpr_shift) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    for (int s = blockIdx.x * gpb + gl; s < C; s += gridDim.x * gpb) {
+        const int r = slot_rank[s];
+        if (r < 0) continue;
+        const V* __restrict__ src = reinterpret_cast<const V*>(cache + (size_t)s * D);
+        V* __restrict__ d = reinterpret_cast<V*>(host + (size_t)r * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = src[cidx];
+    }
+}
+
+static inline int shift_of(int lpr) { int s = 0; while ((1 << s) < lpr) ++s; return s; }
+
+int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, const int32_t* dst_idx, int64_t dst_rows,
+                     const float* src, const int32_t* src_idx, int64_t src_rows, int64_t rows, int max_blocks) {
+    if (rows <= 0) return FC_OK;
+    const int sh = shift_of(c->lpr);
+    const int gpb = 256 >> sh;
+    int64_t blocks = cdiv(rows, gpb);
+    if (blocks > max_blocks) blocks = max_blocks;
+    ProfScope ps(c, prof_item, s);
+    switch (c->vec) {
+        case 4: k_copy_rows<4><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
+        case 2: k_copy_rows<2><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
+        default: k_copy_rows<1><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+int launch_flush_rows(fc_cache* c, hipStream_t s) {
+    const int sh = shift_of(c->lpr);
+    const int gpb = 256 >> sh;
+    int64_t blocks = cdiv(c->C, gpb);
+    if (blocks > 8192) blocks = 8192;
+    ProfScope ps(c, P_FLUSH_ROWS, s);
+    switch (c->vec) {
+        case 4: k_flush_rows<4><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
+        case 2: k_flush_rows<2><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
+        default: k_flush_rows<1><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+}  // namespace fc

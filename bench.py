@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the cache step + EmbeddingBag forward/backward on one MI355X.
+
+A step = cache_prepare + embedding_bag_fwd + embedding_bag_bwd_sgd on one batch of synthetic ids
+(config 2 by default: 26 features in one 10M x 128 fp32 table, batch 16,384 x 26 one-hot ids, cache 1.5%).
+Prints ONE JSON line; see the design doc for the byte model behind `roofline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+LINK_PEAK_GBS = 64.0       # PCIe Gen5 x16, per direction, nominal
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--cache-ratio", type=float, default=0.015)
+    ap.add_argument("--staged", action="store_true", help="use the block (gather / bulk copy / scatter) transmitter")
+    ap.add_argument("--staging-rows", type=int, default=0)
+    ap.add_argument("--profile-steps", type=int, default=50, help="steps of the per-kernel HIP-event pass (0 = skip)")
+    ap.add_argument("--cpu-batches", type=int, default=40, help="batches of the oracle (CPU baseline) leg (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2208_05321_amd import FreqCache
+    from workloads import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU path"
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    w = make_workload(args.config, scale=args.scale, cache_ratio=args.cache_ratio)
+    total_steps = args.warmup + args.steps
+    P = max(0, args.profile_steps)
+    log(f"[bench] workload {w.name}: rows {w.num_rows} dim {w.dim} cache {w.cache_rows} bags/batch {w.bags_per_batch} "
+        f"({time.time() - t0:.1f}s)")
+
+    # a stream of our own (default priority): the library's side stream must not share a hardware queue with it
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
+    cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
+                      warm=False, staged=args.staged, stream=stream)
+    host = cache.host_weight()
+    w.host_table(out=host)
+    cache.warm()
+    log(f"[bench] host table {host.nbytes / 1e9:.2f} GB pinned, filled and warmed ({time.time() - t0:.1f}s)")
+
+    # inputs resident in HBM before the timed region
+    ids_d, off_d, n_ids = [], [], []
+    for t in range(total_steps + P):
+        ids, offsets = w.batch(t)
+        ids_d.append(torch.from_numpy(ids).to(dev))
+        off_d.append(torch.from_numpy(offsets).to(dev))
+        n_ids.append(len(ids))
+    nb = w.bags_per_batch
+    grads = [torch.from_numpy(w.grad(k, nb)).to(dev) for k in range(w.grad_pool)]
+    max_n = max(n_ids)
+    slots = torch.empty(max_n, dtype=torch.int32, device=dev)
+    out = torch.empty((nb, w.dim), dtype=torch.float32, device=dev)
+    log(f"[bench] {total_steps + P} batches on device ({time.time() - t0:.1f}s)")
+
+    stats = []
+
+    def step(t):
+        s = slots[: n_ids[t]]
+        cache.prepare(ids_d[t], off_d[t], out=s)
+        stats.append(cache.stats())
+        cache.embedding_bag_fwd(s, off_d[t], out=out)
+        cache.embedding_bag_bwd_sgd(s, off_d[t], grads[t % len(grads)], w.lr)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for t in range(args.warmup, total_steps):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    cache.check()
+    timed = stats[args.warmup:]
+    tot_ids = sum(s["n_ids"] for s in timed)
+    hit_ratio = sum(s["n_hit_ids"] for s in timed) / max(1, tot_ids)
+    uniq_hit_ratio = sum(s["n_hit_unique"] for s in timed) / max(1, sum(s["n_unique"] for s in timed))
+    value = tot_ids / elapsed
+    ms_per_step = elapsed / args.steps * 1e3
+    mean = {k: float(np.mean([s[k] for s in timed])) for k in ("n_ids", "n_unique", "n_miss", "n_evict")}
+    log(f"[bench] {args.steps} steps in {elapsed:.4f}s: {value / 1e6:.1f} M ids/s, {ms_per_step:.3f} ms/step, "
+        f"hit ratio {hit_ratio:.4f}, per batch unique {mean['n_unique']:.0f} miss {mean['n_miss']:.0f}")
+
+    # ---- per-kernel pass: HIP events on the library's own streams ----
+    kernels = {}
+    roofline = None
+    host_link = None
+    if args.profile_steps > 0:
+        # P further batches of the same trace, each kernel / copy bracketed by HIP events
+        cache.profile(True)
+        pstats = []
+        for t in range(total_steps, total_steps + P):
+            s = slots[: n_ids[t]]
+            cache.prepare(ids_d[t], off_d[t], out=s)
+            pstats.append(cache.stats())
+            cache.embedding_bag_fwd(s, off_d[t], out=out)
+            cache.embedding_bag_bwd_sgd(s, off_d[t], grads[t % len(grads)], w.lr)
+        rep = cache.profile_report()
+        cache.profile(False)
+        R = w.dim * 4
+        n_m = float(np.mean([s["n_ids"] for s in pstats]))
+        u_m = float(np.mean([s["n_unique"] for s in pstats]))
+        m_m = float(np.mean([s["n_miss"] for s in pstats]))
+        e_m = float(np.mean([s["n_evict"] for s in pstats]))
+        nw = -(-w.num_rows // 32)
+        # algorithmic bytes per launch (what the step must move, "byte model")
+        model = {
+            "remap_mark": n_m * (8 + 4 + 4 + 4) + (nb + 1) * 8,            # id, idx_map entry, resident bit word, rank out
+            "rank_count": nw * 4 * 2,
+            "rank_emit": nw * 4 * 2 + m_m * 4 + e_m * (8 + 4 + 4),
+            "evict_gather": e_m * (2 * R + 4),
+            "evict_store": e_m * (2 * R + 4),
+            "free_count": w.cache_rows * 4, "free_assign": w.cache_rows * 4 + m_m * 16,
+            "miss_fill": m_m * (2 * R + 8),
+            "slots_out": n_m * 12,
+            "bag_fwd": n_m * (R + 4) + nb * (R + 8),
+            "bwd_reduce": n_m * 8 + nb * R + 2 * u_m * R,                  # grad read once per bag (one-hot: per id)
+            "sort_hist": n_m * 4, "sort_scatter": n_m * 16,
+        }
+        if w.multi_hot:
+            model["bwd_reduce"] = n_m * 8 + n_m * R + 2 * u_m * R        # every lookup reads its bag's gradient row
+        for name, r in rep.items():
+            avg_us = r["ms"] / r["launches"] * 1e3
+            launches_per_step = r["launches"] / P
+            k = {"avg_us": round(avg_us, 2), "launches_per_step": round(launches_per_step, 2),
+                 "us_per_step": round(avg_us * launches_per_step, 2)}
+            if name in model:
+                per_launch = model[name] / max(launches_per_step, 1e-9)
+                k["alg_bytes_per_launch"] = int(per_launch)
+                k["alg_GBps"] = round(per_launch / (avg_us * 1e-6) / 1e9, 1)
+            kernels[name] = k
+        hbm_kernels = [k for k in kernels if k not in ("miss_fill", "evict_store", "h2d_block", "d2h_block") and "alg_GBps" in kernels[k]]
+        dom = max(hbm_kernels, key=lambda k: kernels[k]["us_per_step"])
+        ach = kernels[dom]["alg_GBps"]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                    "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"]}
+        link = {}
+        for name, direction, rows in (("miss_fill", "h2d", m_m), ("evict_store", "d2h", e_m),
+                                      ("h2d_block", "h2d", m_m), ("d2h_block", "d2h", e_m)):
+            if name in kernels and rows > 0:
+                k = kernels[name]
+                gbs = rows * R / max(k["launches_per_step"], 1e-9) / (k["avg_us"] * 1e-6) / 1e9
+                link[name] = {"direction": direction, "achieved": round(gbs, 1), "peak": LINK_PEAK_GBS, "unit": "GB/s",
+                              "frac": round(gbs / LINK_PEAK_GBS, 4), "bytes_per_step": int(rows * R),
+                              "us_per_step": k["us_per_step"]}
+        host_link = link
+        for name in sorted(kernels, key=lambda k: -kernels[k]["us_per_step"]):
+            log(f"[bench]   {name:14s} {kernels[name]}")
+
+    # ---- CPU baseline: the oracle as it stands, one core, a bounded sample of the same trace ----
+    cpu_baseline = None
+    if args.cpu_batches > 0:
+        from oracle import Oracle
+        S = min(args.cpu_batches, total_steps)
+        host_o = np.empty_like(host)
+        w.host_table(out=host_o)
+        orc = Oracle(w.freq_rank, host_o, w.cache_rows, warm=True)
+        batches = [w.batch(t) for t in range(S)]
+        gpool = [w.grad(k, nb).copy() for k in range(w.grad_pool)]
+        t_cpu = 0.0
+        same = True
+        for t in range(S):
+            ids, offsets = batches[t]
+            a = time.perf_counter()
+            so = orc.prepare(ids, offsets)
+            orc.embedding_bag_fwd(so, offsets)
+            orc.embedding_bag_bwd_sgd(so, offsets, gpool[t % len(gpool)], w.lr)
+            t_cpu += time.perf_counter() - a
+            same &= orc.stats() == stats[t]
+        cpu_baseline = {"value": round(sum(len(b[0]) for b in batches) / t_cpu, 1), "unit": "ids/s", "cores": 1,
+                        "kind": "oracle", "sample": f"first {S} batches of the same trace (prepare+fwd+bwd, warm start)",
+                        "host_cores_available": os.cpu_count(), "gpu_stats_identical_on_sample": bool(same)}
+        log(f"[bench] oracle: {cpu_baseline['value'] / 1e6:.2f} M ids/s on 1 core over {S} batches; stats identical: {same}")
+        orc.close()
+
+    result = {
+        "metric": "ids/sec through cache prepare + EmbeddingBag fwd/bwd at 1.5% cache",
+        "value": round(value, 1), "unit": "ids/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.num_features} features in one {w.num_rows} x {w.dim} fp32 table, "
+                               f"batch {w.samples} x {w.num_features} {'multi-hot' if w.multi_hot else 'one-hot'} ids, "
+                               f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
+                   "transmitter": "staged-block" if args.staged else "direct",
+                   "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
+                   "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
+        "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5),
+        "roofline": roofline, "host_link": host_link, "kernels": kernels, "cpu_baseline": cpu_baseline,
+    }
+    cache.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

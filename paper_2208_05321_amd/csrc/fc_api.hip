@@ -3,6 +3,7 @@
 #include "fc_internal.h"
 
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 #include <vector>
 
@@ -10,7 +11,7 @@ namespace fc {
 
 // ---- profiling ----
 static const char* const kProfNames[P_COUNT] = {
-    "remap_mark", "rank_count", "rank_plan", "rank_emit", "evict_gather", "evict_store", "free_pick",
+    "remap_mark", "rank_count", "rank_plan", "rank_emit", "evict_gather", "evict_store", "free_count", "free_assign",
     "miss_fill", "slots_out", "bag_fwd", "sort_hist", "sort_scan", "sort_scatter", "bwd_reduce", "bwd_fixup",
     "h2d_block", "d2h_block", "flush_rows"};
 
@@ -70,7 +71,6 @@ static int reset_state(fc_cache* c, bool warm) {
     k_iota_or_neg<<<256, 256, 0, st>>>(c->slot_rank, c->C, warm ? c->C : 0);
     k_bits_prefix<<<256, 256, 0, st>>>(c->ubits, words, 0);
     k_bits_prefix<<<256, 256, 0, st>>>(c->rbits, words, warm ? c->C : 0);
-    k_bits_prefix<<<64, 256, 0, st>>>(c->fbits, c->CW, warm ? 0 : c->C);
     k_set_ctl<<<1, 1, 0, st>>>(c->ctl, warm ? 0 : (int)c->C);
     FC_HIP(hipGetLastError());
     if (warm) FC_HIP(hipMemcpyAsync(c->cache, c->host, (size_t)c->C * c->D * 4, hipMemcpyHostToDevice, st));
@@ -86,7 +86,7 @@ static void destroy(fc_cache* c) {
     (void)hipSetDevice(c->device);
     if (c->stream || c->side) (void)hipDeviceSynchronize();
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
-                    (void*)c->rbits, (void*)c->fbits, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
+                    (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
                     (void*)c->miss_ranks, (void*)c->vrank, (void*)c->vslot, (void*)c->fill_slots, (void*)c->rbuf,
                     (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->keysA, (void*)c->valsA,
                     (void*)c->keysB, (void*)c->valsB, (void*)c->ghist, (void*)c->dtot, (void*)c->part, (void*)c->pmeta})
@@ -112,8 +112,9 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (staging_rows <= 0) staging_rows = C < 131072 ? C : 131072;
     if (staging_rows > C) staging_rows = C;
     c->staging_rows = staging_rows;
+    if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }
+    if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e) != 0;
     c->NB = cdiv(cdiv(N, 32), RT_WORDS);
-    c->CW = cdiv(C, 32);
     const size_t words = (size_t)c->NB * RT_WORDS;
 
     // host table
@@ -137,7 +138,8 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipMalloc((void**)&c->cache, (size_t)C * D * 4));
     FC_HIP(hipMalloc((void**)&c->ubits, words * 4));
     FC_HIP(hipMalloc((void**)&c->rbits, words * 4));
-    FC_HIP(hipMalloc((void**)&c->fbits, (size_t)c->CW * 4));
+    FC_HIP(hipMalloc((void**)&c->tcount, (size_t)cdiv(C, 1024) * 4));
+    FC_HIP(hipMalloc((void**)&c->hitpart, 256 * 4));
     FC_HIP(hipMalloc((void**)&c->bsum, (size_t)c->NB * 3 * 4));
     FC_HIP(hipMalloc((void**)&c->moff, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->vtake, (size_t)c->NB * 4));

@@ -41,7 +41,7 @@ struct HostCtl {
 };
 
 enum ProfItem {
-    P_REMAP_MARK = 0, P_RANK_COUNT, P_RANK_PLAN, P_RANK_EMIT, P_EVICT_GATHER, P_EVICT_STORE, P_FREE_PICK,
+    P_REMAP_MARK = 0, P_RANK_COUNT, P_RANK_PLAN, P_RANK_EMIT, P_EVICT_GATHER, P_EVICT_STORE, P_FREE_COUNT, P_FREE_PICK,
     P_MISS_FILL, P_SLOTS_OUT, P_BAG_FWD, P_SORT_HIST, P_SORT_SCAN, P_SORT_SCATTER, P_BWD_REDUCE, P_BWD_FIXUP,
     P_H2D_BLOCK, P_D2H_BLOCK, P_FLUSH_ROWS, P_COUNT
 };
@@ -59,6 +59,8 @@ struct fc_cache {
     hipStream_t stream = nullptr, side = nullptr;
     hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
     bool evict_pending = false;
+    int evict_blocks = 16;          // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
+    bool evict_early = false;       // start that kernel before the miss fill (tuning: FC_EVICT_EARLY=1)
 
     // row geometry: VEC floats per lane access, LPR lanes per row
     int vec = 1, lpr = 1;
@@ -70,9 +72,9 @@ struct fc_cache {
     float* cache = nullptr;         // [C][D]
     uint32_t* ubits = nullptr;      // rank-space bitmap: rows used by the current batch (zero between calls)
     uint32_t* rbits = nullptr;      // rank-space bitmap: resident rows
-    uint32_t* fbits = nullptr;      // slot-space bitmap: empty slots
+    int32_t* tcount = nullptr;      // empty slots per tile of 1024 slots
+    int32_t* hitpart = nullptr;     // [256] per-workgroup access-level hit counts of the marking kernel
     int64_t NB = 0;                 // rank-space tiles
-    int64_t CW = 0;                 // words of fbits (padded to 1024)
     int32_t* bsum = nullptr;        // [3][NB] per-tile counts: used, missing, evictable
     int32_t* moff = nullptr;        // [NB] output offset of a tile's missing ranks
     int32_t* vtake = nullptr;       // [NB] victims taken from a tile

@@ -2,10 +2,10 @@
 // chain of gfx950 kernels.
 //
 // The paper's prototype strings together framework calls (unique, isin, nonzero, index_fill, argsort,
-// index_copy).  Here the same decisions come out of three bitmaps and popcount scans, with no sort:
-//   ubits  rank space, rows used by this batch        -> unique() is "which bits are set", ascending for free
-//   rbits  rank space, rows resident in HBM           -> missing = ubits & ~rbits, evictable = rbits & ~ubits
-//   fbits  slot space, empty slots                    -> the i-th missing rank takes the i-th set bit
+// index_copy).  Here the same decisions come out of two rank-space bitmaps and popcount scans, with no sort:
+//   ubits  rows used by this batch        -> unique() is "which bits are set", ascending for free
+//   rbits  rows resident in HBM           -> missing = ubits & ~rbits, evictable = rbits & ~ubits
+// and the empty slots are read off the slot->rank map: the i-th missing rank takes the i-th empty slot.
 // "The evict_num largest cpu_row_idx not used by the batch" (LFU by static frequency rank) is the top
 // evict_num set bits of (rbits & ~ubits): a suffix count over bitmap tiles finds the threshold tile.
 #include "fc_internal.h"
@@ -17,38 +17,71 @@ namespace fc {
 
 // ---------------------------------------------------------------------------------------------------------
 // K1  ids -> frequency rank (idx_map lookup), mark the rank in ubits, count access-level hits, check offsets.
+//
+// Frequent ids are by construction the LOW ranks, and they are the ones repeated thousands of times in a
+// batch.  Device-scope atomics on one address serialise at the memory side (~100 ns each on this part), so
+// the low end of rank space is first marked in a per-workgroup LDS bitmap (fast LDS atomics) and merged into
+// the global bitmap once per workgroup; only the long tail of rare ranks goes to global atomics directly.
+// At most MARK_MAX_BLOCKS workgroups run, so a hot word sees at most that many global atomics.
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_remap_mark(const int64_t* __restrict__ ids, int n,
-                                                    const int64_t* __restrict__ offsets, int num_bags,
-                                                    const int32_t* __restrict__ freq_rank, int64_t N, uint32_t* ubits,
-                                                    const uint32_t* __restrict__ rbits, int32_t* __restrict__ rbuf,
-                                                    Ctl* ctl) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    bool hit = false;
+constexpr int MARK_THREADS = 1024;
+constexpr int MARK_LDS_WORDS = 12288;      // 48 KB: ranks below 393,216
+constexpr int MARK_MAX_BLOCKS = 256;
+
+__global__ __launch_bounds__(MARK_THREADS) void k_remap_mark(const int64_t* __restrict__ ids, int n,
+                                                             const int64_t* __restrict__ offsets, int num_bags,
+                                                             const int32_t* __restrict__ freq_rank, int64_t N,
+                                                             uint32_t* ubits, const uint32_t* __restrict__ rbits,
+                                                             int32_t* __restrict__ rbuf, Ctl* ctl,
+                                                             int32_t* __restrict__ hitpart, int per_block,
+                                                             int lds_words) {
+    __shared__ uint32_t low[MARK_LDS_WORDS];
+    __shared__ int red[MARK_THREADS / 64];
+    const int tid = threadIdx.x;
+    for (int w = tid; w < lds_words; w += MARK_THREADS) low[w] = 0;
+    __syncthreads();
+    const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
+    const int64_t begin = (int64_t)blockIdx.x * per_block;
+    const int64_t end = begin + per_block < work ? begin + per_block : work;
+    int hits = 0;
     uint32_t flags = 0;
-    if (i < n) {
-        const int64_t id = ids[i];
-        int r = -1;
-        if (id < 0 || id >= N) {
-            flags |= EF_ID_RANGE;
-        } else {
-            r = freq_rank[id];
-            const uint32_t w = (uint32_t)r >> 5, bit = 1u << (r & 31);
-            // Bits are only ever set during this kernel, so a plain read that already sees the bit is
-            // final; hot rows then cost one read instead of thousands of same-address atomics.
-            if (!(ubits[w] & bit)) atomicOr(&ubits[w], bit);
-            hit = (rbits[w] & bit) != 0;
+    for (int64_t i = begin + tid; i < end; i += MARK_THREADS) {
+        if (i < n) {
+            const int64_t id = ids[i];
+            int r = -1;
+            if (id < 0 || id >= N) {
+                flags |= EF_ID_RANGE;
+            } else {
+                r = freq_rank[id];
+                const uint32_t w = (uint32_t)r >> 5, bit = 1u << (r & 31);
+                if (w < (uint32_t)lds_words) atomicOr(&low[w], bit);
+                // rare ranks: bits are only ever set during this kernel, so a read that sees the bit is final
+                else if (!(ubits[w] & bit)) atomicOr(&ubits[w], bit);
+                hits += (rbits[w] & bit) != 0;
+            }
+            rbuf[i] = r;
         }
-        rbuf[i] = r;
+        if (i <= num_bags) {
+            const int64_t o = offsets[i];
+            if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
+            if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
+            if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
+        }
     }
-    if (i <= num_bags) {
-        const int64_t o = offsets[i];
-        if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
-        if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
-        if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
+    __syncthreads();
+    for (int w = tid; w < lds_words; w += MARK_THREADS) {
+        const uint32_t v = low[w];
+        if (v && (v & ~ubits[w])) atomicOr(&ubits[w], v);
     }
-    const uint64_t hb = __ballot(hit);
-    if ((threadIdx.x & 63) == 0 && hb) atomicAdd(&ctl->hit_ids, __popcll(hb));
+    hits = wave_sum(hits);
+    if ((tid & 63) == 0) red[tid >> 6] = hits;
+    __syncthreads();
+    if (tid == 0) {
+        int s = 0;
+#pragma unroll
+        for (int k = 0; k < MARK_THREADS / 64; ++k) s += red[k];
+        hitpart[blockIdx.x] = s;
+    }
     if (flags) atomicOr(&ctl->err_flags, flags);
 }
 
@@ -82,9 +115,12 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restri
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
                                                     HostCtl* hctl, int32_t* __restrict__ moff,
-                                                    int32_t* __restrict__ vtake, int32_t* __restrict__ voff) {
+                                                    int32_t* __restrict__ vtake, int32_t* __restrict__ voff,
+                                                    const int32_t* __restrict__ hitpart, int nmark) {
     __shared__ int lds[16];
     const int tid = threadIdx.x;
+    int hits;
+    (void)block_excl_scan<1024>(tid < nmark ? hitpart[tid] : 0, hits, lds);   // nmark <= 256
     int carryM = 0, totU = 0;
     for (int base = 0; base < NB; base += 1024) {
         const int b = base + tid;
@@ -126,7 +162,6 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
     }
     __syncthreads();
     if (tid == 0) {
-        const int hits = ctl->hit_ids;
         ctl->status = status;
         ctl->n_unique = totU;
         ctl->n_miss = M;
@@ -149,7 +184,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
                                                           const int32_t* __restrict__ voff,
                                                           int32_t* __restrict__ miss_ranks, int32_t* __restrict__ vrank,
                                                           int32_t* __restrict__ vslot, int32_t* rank_slot,
-                                                          int32_t* slot_rank, uint32_t* fbits, int C) {
+                                                          int32_t* slot_rank, int C) {
     __shared__ int lds[RT_THREADS / 64];
     const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
     const uint4 u4 = ubits4[idx];
@@ -205,10 +240,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
                         vrank[j] = rank;
                         vslot[j] = slot;
                         rank_slot[rank] = -1;
-                        if ((unsigned)slot < (unsigned)C) {   // always true while the two maps are inverse
-                            slot_rank[slot] = -1;
-                            atomicOr(&fbits[slot >> 5], 1u << (slot & 31));
-                        }
+                        if ((unsigned)slot < (unsigned)C) slot_rank[slot] = -1;   // always true: the maps are inverse
                         vw[k] |= 1u << bit;
                     }
                     ++q;
@@ -225,36 +257,44 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
 
 // ---------------------------------------------------------------------------------------------------------
 // K6  the i-th missing rank takes the i-th lowest empty slot; both index maps are updated.
+//     a) empty slots per tile of FREE_TILE slots;  b) each tile ranks its empty slots after the tiles below it.
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_free_pick(uint32_t* fbits, int CW, int M,
-                                                    const int32_t* __restrict__ miss_ranks,
-                                                    int32_t* __restrict__ fill_slots, int32_t* slot_rank,
-                                                    int32_t* rank_slot) {
-    __shared__ int lds[16];
-    const int tid = threadIdx.x;
-    int base = 0;
-    for (int w0 = 0; w0 < CW && base < M; w0 += 1024) {
-        const int w = w0 + tid;
-        uint32_t word = w < CW ? fbits[w] : 0u;
-        const int cnt = __popc(word);
-        int tot;
-        int j = base + block_excl_scan<1024>(cnt, tot, lds);
-        if (cnt && j < M) {
-            uint32_t keep = word;
-            while (word && j < M) {
-                const int bit = __ffs(word) - 1;
-                const int slot = w * 32 + bit;
-                const int r = miss_ranks[j];
-                fill_slots[j] = slot;
-                slot_rank[slot] = r;
-                rank_slot[r] = slot;
-                keep &= ~(1u << bit);
-                word &= word - 1;
-                ++j;
-            }
-            fbits[w] = keep;
-        }
-        base += tot;
+constexpr int FREE_TILE = 1024;
+
+__global__ __launch_bounds__(FREE_TILE) void k_free_count(const int32_t* __restrict__ slot_rank, int C,
+                                                          int32_t* __restrict__ tcount) {
+    __shared__ int red[FREE_TILE / 64];
+    const int s = blockIdx.x * FREE_TILE + threadIdx.x;
+    const bool empty = s < C && slot_rank[s] == -1;
+    const uint64_t b = __ballot(empty);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __popcll(b);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < FREE_TILE / 64; ++k) t += red[k];
+        tcount[blockIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(FREE_TILE) void k_free_assign(int32_t* slot_rank, int C, const int32_t* __restrict__ tcount,
+                                                           int M, const int32_t* __restrict__ miss_ranks,
+                                                           int32_t* __restrict__ fill_slots, int32_t* rank_slot) {
+    __shared__ int lds[FREE_TILE / 64];
+    int part = 0;
+    for (int g = threadIdx.x; g < (int)blockIdx.x; g += FREE_TILE) part += tcount[g];
+    int base;
+    (void)block_excl_scan<FREE_TILE>(part, base, lds);
+    if (base >= M) return;                                   // all missing rows were placed in lower tiles
+    const int s = blockIdx.x * FREE_TILE + threadIdx.x;
+    const bool empty = s < C && slot_rank[s] == -1;
+    int tot;
+    const int j = base + block_excl_scan<FREE_TILE>(empty ? 1 : 0, tot, lds);
+    if (empty && j < M) {
+        const int r = miss_ranks[j];
+        fill_slots[j] = s;
+        slot_rank[s] = r;
+        rank_slot[r] = s;
     }
 }
 
@@ -279,18 +319,29 @@ static int ensure_rbuf(fc_cache* c, int64_t n) {
 }
 
 // Evicted rows, default transmitter: gather into a device block on the caller's stream (so the slots can be
-// refilled at once), then store the block into the mapped host table on the side stream, off the critical path.
-static int evict_direct(fc_cache* c, int64_t need) {
+// refilled at once); the block is stored into the mapped host table by a small kernel on the side stream.
+// Zero-copy stores that saturate the host link stall every other memory operation of the compute units they
+// run on (and delay reads in the other direction), so the store kernel is confined to a few workgroups
+// (c->evict_blocks) and, unless c->evict_early, starts only once the miss fill is done, running under the
+// forward / backward kernels.  Blocks before the last are stored at once because the one block buffer must be
+// free again for the next gather.
+static int store_block(fc_cache* c, int64_t off, int64_t rows) {
+    FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
+    FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
+    FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->vrank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, c->evict_blocks));
+    FC_HIP(hipEventRecord(c->ev_evict_done, c->side));
+    c->evict_pending = true;
+    return FC_OK;
+}
+
+static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* last_rows) {
     const int64_t S = c->staging_rows;
     for (int64_t off = 0; off < need; off += S) {
         const int64_t rows = need - off < S ? need - off : S;
         if (off > 0) FC_HIP(hipStreamWaitEvent(c->stream, c->ev_evict_done, 0));   // block buffer is being read
         FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
-        FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
-        FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
-        FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->vrank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, 512));
-        FC_HIP(hipEventRecord(c->ev_evict_done, c->side));
-        c->evict_pending = true;
+        if (off + rows >= need && !c->evict_early) { *last_off = off; *last_rows = rows; break; }
+        FC_TRY(store_block(c, off, rows));
     }
     return FC_OK;
 }
@@ -339,17 +390,17 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     hipStream_t st = c->stream;
-    // Last batch's evicted rows must have reached the host table before its block buffer / lists are reused
-    // and before any of those rows could be fetched again.
-    if (c->evict_pending) {
-        FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0));
-        c->evict_pending = false;
-    }
     const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
+    int64_t nmark = cdiv(work, 4 * MARK_THREADS);
+    if (nmark > MARK_MAX_BLOCKS) nmark = MARK_MAX_BLOCKS;
+    const int64_t per_block = cdiv(cdiv(work, nmark), MARK_THREADS) * MARK_THREADS;
+    nmark = cdiv(work, per_block);
+    const int64_t words = c->NB * RT_WORDS;
     {
         ProfScope ps(c, P_REMAP_MARK, st);
-        k_remap_mark<<<(unsigned)cdiv(work, 256), 256, 0, st>>>(ids, (int)n, offsets, (int)num_bags, c->freq_rank, c->N,
-                                                               c->ubits, c->rbits, c->rbuf, c->ctl);
+        k_remap_mark<<<(unsigned)nmark, MARK_THREADS, 0, st>>>(ids, (int)n, offsets, (int)num_bags, c->freq_rank, c->N, c->ubits,
+                                                              c->rbits, c->rbuf, c->ctl, c->hitpart, (int)per_block,
+                                                              (int)(words < MARK_LDS_WORDS ? words : MARK_LDS_WORDS));
     }
     {
         ProfScope ps(c, P_RANK_COUNT, st);
@@ -357,13 +408,19 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     }
     {
         ProfScope ps(c, P_RANK_PLAN, st);
-        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff);
+        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff, c->hitpart, (int)nmark);
     }
     FC_HIP(hipEventRecord(c->ev_plan, st));
+    // Last batch's evicted rows must have reached the host table before the victim lists and the block buffer
+    // are reused and before any of those rows could be fetched again; the kernels above do not care.
+    if (c->evict_pending) {
+        FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0));
+        c->evict_pending = false;
+    }
     {
         ProfScope ps(c, P_RANK_EMIT, st);
         k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, c->ctl, c->moff, c->vtake, c->voff,
-                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, c->fbits, (int)c->C);
+                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C);
     }
     FC_HIP(hipGetLastError());
     FC_HIP(hipEventSynchronize(c->ev_plan));
@@ -381,15 +438,23 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
         if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
         FC_HIP(hipStreamSynchronize(st));
     }
-    if (need > 0) FC_TRY(staged ? evict_staged(c, need, c->list_pin + c->C) : evict_direct(c, need));
+    int64_t last_off = 0, last_rows = 0;
+    if (need > 0) FC_TRY(staged ? evict_staged(c, need, c->list_pin + c->C) : evict_direct(c, need, &last_off, &last_rows));
     if (M > 0) {
         {
+            const unsigned tiles = (unsigned)cdiv(c->C, FREE_TILE);
+            {
+                ProfScope ps(c, P_FREE_COUNT, st);
+                k_free_count<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount);
+            }
             ProfScope ps(c, P_FREE_PICK, st);
-            k_free_pick<<<1, 1024, 0, st>>>(c->fbits, (int)c->CW, (int)M, c->miss_ranks, c->fill_slots, c->slot_rank, c->rank_slot);
+            k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
+                                                      c->rank_slot);
         }
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
     }
+    if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
     if (n > 0) {
         ProfScope ps(c, P_SLOTS_OUT, st);
         k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);

@@ -1,0 +1,260 @@
+"""`-m gpu`: edge cases, error paths and odd shapes of the HIP library, against the oracle, through the C ABI."""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+
+from tests.parity import run_parity, assert_close, compare_prepare
+from tests.tiny_workload import TinyWorkload
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2208_05321_amd import load_library
+    load_library()
+    return torch
+
+
+def make_pair(w, warm=True, **kw):
+    from oracle import Oracle
+    from paper_2208_05321_amd import FreqCache
+    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, warm=False, **kw)
+    host = gpu.host_weight()
+    w.host_table(out=host)
+    if warm:
+        gpu.warm()
+    orc = Oracle(w.freq_rank, host.copy(), w.cache_rows, warm=warm)
+    return gpu, orc
+
+
+@pytest.mark.parametrize("dim", [1, 5, 6, 16, 64, 260])
+@pytest.mark.parametrize("warm", [True, False])
+def test_odd_dims_multi_hot_with_empty_bags(torch_cuda, dim, warm):
+    """Every vector width (1, 2, 4 floats per lane), rows wider than one pass of 64 lanes, empty bags,
+    ids repeated inside a bag."""
+    log(f"dim {dim} warm {warm}")
+    w = TinyWorkload(num_rows=3000, dim=dim, cache_rows=260, seed=dim, bags=97, max_bag=6, distinct_cap=200)
+    run_parity(w, 12, warm=warm)
+
+
+def test_hot_rows_long_runs(torch_cuda):
+    """A few ids take most of 20k lookups: runs of one slot span hundreds of backward chunks."""
+    w = TinyWorkload(num_rows=50000, dim=128, cache_rows=900, seed=3, bags=4000, max_bag=9, hot=[7, 11, 13],
+                     distinct_cap=800, allow_empty=False)
+    run_parity(w, 5, warm=True)
+
+
+def test_single_id_batches(torch_cuda):
+    """Degenerate: every lookup is the same row (one run over the whole batch), and a one-lookup batch."""
+    torch = torch_cuda
+    w = TinyWorkload(num_rows=500, dim=32, cache_rows=8, seed=5, multi_hot=False)
+    gpu, orc = make_pair(w, warm=True)
+    dev = torch.device("cuda:0")
+    for n, the_id in ((1, 123), (10000, 77), (4097, 77), (33, 499)):
+        ids = np.full(n, the_id, dtype=np.int64)
+        off = np.arange(n + 1, dtype=np.int64)
+        g = np.random.default_rng(n).standard_normal((n, w.dim)).astype(np.float32)
+        so = orc.prepare(ids, off)
+        sd = gpu.prepare(torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev))
+        compare_prepare(gpu, orc, sd.cpu().numpy(), so, n)
+        od = gpu.embedding_bag_fwd(sd, torch.from_numpy(off).to(dev))
+        assert_close(od.cpu().numpy(), orc.embedding_bag_fwd(so, off), "fwd")
+        gpu.embedding_bag_bwd_sgd(sd, torch.from_numpy(off).to(dev), torch.from_numpy(g).to(dev), 0.01)
+        orc.embedding_bag_bwd_sgd(so, off, g, 0.01)
+        assert_close(gpu.rows(), orc.cache, f"rows after n={n}")
+    gpu.check()
+    gpu.close()
+
+
+def test_whole_cache_needed_and_all_hits(torch_cuda):
+    """|unique| == cache_rows (every other resident row is evicted), then a batch of pure hits."""
+    torch = torch_cuda
+    w = TinyWorkload(num_rows=4000, dim=16, cache_rows=300, seed=9, multi_hot=False)
+    gpu, orc = make_pair(w, warm=True)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(0)
+    for t in range(6):
+        if t % 2 == 0:
+            ids = rng.permutation(w.num_rows)[: w.cache_rows].astype(np.int64)       # exactly C distinct rows
+        else:
+            res = np.nonzero(orc.rank_slot >= 0)[0]
+            ids = w.inv_rank[res][rng.integers(0, len(res), size=500)].astype(np.int64)   # all resident
+        off = np.arange(len(ids) + 1, dtype=np.int64)
+        so = orc.prepare(ids, off)
+        sd = gpu.prepare(torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev))
+        compare_prepare(gpu, orc, sd.cpu().numpy(), so, t)
+        s = gpu.stats()
+        if t % 2 == 0:
+            assert s["n_unique"] == w.cache_rows
+        else:
+            assert s["n_miss"] == 0 and s["n_evict"] == 0 and s["n_hit_ids"] == 500
+    gpu.close()
+
+
+def test_error_paths_leave_state_unchanged(torch_cuda):
+    torch = torch_cuda
+    from paper_2208_05321_amd import FreqCacheError
+    w = TinyWorkload(num_rows=2000, dim=8, cache_rows=50, seed=1, multi_hot=True, bags=20, max_bag=3, distinct_cap=40)
+    gpu, orc = make_pair(w, warm=True)
+    dev = torch.device("cuda:0")
+
+    def dev_t(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    def step(t):
+        ids, off = w.batch(t)
+        so = orc.prepare(ids, off)
+        sd = gpu.prepare(dev_t(ids), dev_t(off))
+        compare_prepare(gpu, orc, sd.cpu().numpy(), so, t)
+        g = w.grad(t, len(off) - 1)
+        gpu.embedding_bag_bwd_sgd(sd, dev_t(off), dev_t(g), 0.1)
+        orc.embedding_bag_bwd_sgd(so, off, g, 0.1)
+
+    step(0)
+    step(1)
+    sr0, rs0 = gpu.state()
+    rows0 = gpu.rows()
+    host0 = gpu.host_weight().copy()
+    stats0 = gpu.stats()
+
+    def unchanged():
+        sr, rs = gpu.state()
+        return (np.array_equal(sr, sr0) and np.array_equal(rs, rs0) and np.array_equal(gpu.rows(), rows0)
+                and np.array_equal(gpu.host_weight(), host0) and gpu.stats() == stats0)
+
+    one = np.arange(4, dtype=np.int64)
+    cases = [
+        ("BATCH_EXCEEDS_CACHE", np.arange(51, dtype=np.int64), np.arange(52, dtype=np.int64)),
+        ("ID_OUT_OF_RANGE", np.array([1, 2000, 3], dtype=np.int64), one),
+        ("ID_OUT_OF_RANGE", np.array([1, -1, 3], dtype=np.int64), one),
+        ("BAD_OFFSETS", np.array([1, 2, 3], dtype=np.int64), np.array([0, 2, 1, 3], dtype=np.int64)),
+        ("BAD_OFFSETS", np.array([1, 2, 3], dtype=np.int64), np.array([1, 2, 3, 3], dtype=np.int64)),
+        ("BAD_OFFSETS", np.array([1, 2, 3], dtype=np.int64), np.array([0, 1, 2, 2], dtype=np.int64)),
+        # offsets are checked before ids (same precedence as the oracle)
+        ("BAD_OFFSETS", np.array([1, 9999, 3], dtype=np.int64), np.array([0, 2, 1, 3], dtype=np.int64)),
+    ]
+    from oracle import OracleError
+    for name, ids, off in cases:
+        with pytest.raises(FreqCacheError) as e:
+            gpu.prepare(dev_t(ids), dev_t(off))
+        assert e.value.name == name, (name, e.value.name)
+        with pytest.raises(OracleError) as eo:
+            orc.prepare(ids, off)
+        assert eo.value.name == name
+        assert unchanged(), f"state changed by a failing call ({name})"
+    # empty batch with three empty bags: fine, nothing moves
+    sd = gpu.prepare(dev_t(np.empty(0, np.int64)), dev_t(np.zeros(4, np.int64)))
+    assert sd.numel() == 0
+    out = gpu.embedding_bag_fwd(sd, dev_t(np.zeros(4, np.int64)))
+    assert out.shape == (3, 8) and float(out.abs().max()) == 0.0
+    gpu.embedding_bag_bwd_sgd(sd, dev_t(np.zeros(4, np.int64)), dev_t(np.ones((3, 8), np.float32)), 0.1)
+    orc.prepare(np.empty(0, np.int64), np.zeros(4, np.int64))
+    sr, rs = gpu.state()
+    assert np.array_equal(sr, sr0) and np.array_equal(gpu.rows(), rows0)
+    # the cache still works and still agrees with the oracle afterwards
+    step(2)
+    step(3)
+    gpu.check()
+    gpu.flush()
+    orc.flush()
+    assert_close(gpu.host_weight(), orc.host, "host table")
+    gpu.close()
+
+
+def test_bad_slots_are_reported_not_followed(torch_cuda):
+    torch = torch_cuda
+    from paper_2208_05321_amd import FreqCacheError
+    w = TinyWorkload(num_rows=500, dim=16, cache_rows=20, seed=2)
+    gpu, _ = make_pair(w, warm=True)
+    dev = torch.device("cuda:0")
+    rows0 = gpu.rows()
+    slots = torch.tensor([0, 5, 20, -3, 7], dtype=torch.int32, device=dev)
+    off = torch.tensor([0, 2, 5], dtype=torch.int64, device=dev)
+    out = gpu.embedding_bag_fwd(slots, off)
+    with pytest.raises(FreqCacheError) as e:
+        gpu.check()
+    assert e.value.name == "BAD_SLOT"
+    ref = np.stack([rows0[0] + rows0[5], rows0[7]])
+    assert_close(out.cpu().numpy(), ref, "valid slots still pooled")
+    gpu.check()                                     # the flag is cleared once reported
+    g = torch.ones((2, 16), dtype=torch.float32, device=dev)
+    gpu.embedding_bag_bwd_sgd(slots, off, g, 0.5)
+    with pytest.raises(FreqCacheError):
+        gpu.check()
+    rows1 = gpu.rows()
+    expect = rows0.copy()
+    for s in (0, 5, 7):
+        expect[s] = expect[s] - np.float32(0.5) * np.float32(1.0)
+    assert_close(rows1, expect, "only valid slots updated")
+    gpu.close()
+
+
+def test_create_argument_errors(torch_cuda):
+    torch = torch_cuda
+    from paper_2208_05321_amd import FreqCache, FreqCacheError
+    fr = np.arange(100, dtype=np.int32)
+    for kw, name in ((dict(cache_rows=0), "INVALID_ARG"), (dict(cache_rows=101), "INVALID_ARG"),
+                     (dict(dim=0), "INVALID_ARG")):
+        args = dict(num_rows=100, dim=4, cache_rows=10)
+        args.update(kw)
+        with pytest.raises(FreqCacheError) as e:
+            FreqCache(args["num_rows"], args["dim"], args["cache_rows"], fr)
+        assert e.value.name == name
+    bad = fr.copy()
+    bad[3] = 4
+    with pytest.raises(FreqCacheError) as e:
+        FreqCache(100, 4, 10, bad)
+    assert e.value.name == "NOT_PERMUTATION"
+    # warm-up needs a table to load from
+    with pytest.raises(FreqCacheError) as e:
+        FreqCache(100, 4, 10, fr, host_weight=None, warm=True)
+    assert e.value.name == "INVALID_ARG"
+    # pageable memory is refused
+    L = __import__("paper_2208_05321_amd").load_library()
+    h = ctypes.c_void_p()
+    pageable = np.zeros((100, 4), dtype=np.float32)
+    rc = L.cache_create(100, 4, 10, fr.ctypes.data, pageable.ctypes.data, 0, 0, None, ctypes.byref(h))
+    assert rc == -9
+    # a pinned torch tensor is accepted and used in place
+    host = torch.empty((100, 4), dtype=torch.float32, pin_memory=True)
+    host.copy_(torch.arange(400, dtype=torch.float32).reshape(100, 4))
+    c = FreqCache(100, 4, 10, fr, host_weight=host, warm=True)
+    assert np.array_equal(c.rows(), host.numpy()[:10])
+    assert c.host_weight().ctypes.data == host.data_ptr()
+    c.close()
+
+
+def test_backward_is_reproducible(torch_cuda):
+    """No floating-point atomics: two runs over the same inputs give bit-identical cached rows."""
+    torch = torch_cuda
+    w = make_workload("c5", scale=0.02, cache_ratio=0.03)
+    dev = torch.device("cuda:0")
+    results = []
+    for run in range(2):
+        gpu, _ = make_pair(w, warm=True)
+        for t in range(3):
+            ids, off = w.batch(t)
+            sd = gpu.prepare(torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev))
+            gpu.embedding_bag_bwd_sgd(sd, torch.from_numpy(off).to(dev), torch.from_numpy(w.grad(t, len(off) - 1)).to(dev), w.lr)
+        results.append(gpu.rows())
+        gpu.close()
+    assert np.array_equal(results[0], results[1])
+
+
+@pytest.mark.slow
+def test_config2_full_size(torch_cuda):
+    """Config 2 at its real size (10M x 128 table, 425,984 ids per batch, 150k-row cache), as bench.py runs it."""
+    log("config 2, full size")
+    w = make_workload("c2")
+    tot = run_parity(w, 10, warm=True, deep_every=3, values_every=3, log=log)
+    assert 0.85 < tot["hit_ids"] / tot["ids"] < 0.95

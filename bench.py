@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--staged", action="store_true", help="use the block (gather / bulk copy / scatter) transmitter")
     ap.add_argument("--staging-rows", type=int, default=0)
     ap.add_argument("--profile-steps", type=int, default=50, help="steps of the per-kernel HIP-event pass (0 = skip)")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="issue one plain device copy of this many MiB first (reference point for rocprofv3 --pmc byte counters)")
     ap.add_argument("--cpu-batches", type=int, default=40, help="batches of the oracle (CPU baseline) leg (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,6 +82,14 @@ def main():
     slots = torch.empty(max_n, dtype=torch.int32, device=dev)
     out = torch.empty((nb, w.dim), dtype=torch.float32, device=dev)
     log(f"[bench] {total_steps + P} batches on device ({time.time() - t0:.1f}s)")
+
+    if args.calib_copy_mb > 0:
+        a = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                      # reads and writes exactly calib_copy_mb MiB each
+        torch.cuda.synchronize()
+        del a, b
 
     stats = []
 

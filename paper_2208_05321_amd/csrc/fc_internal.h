@@ -59,8 +59,9 @@ struct fc_cache {
     hipStream_t stream = nullptr, side = nullptr;
     hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
     bool evict_pending = false;
-    int evict_blocks = 16;          // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
-    bool evict_early = false;       // start that kernel before the miss fill (tuning: FC_EVICT_EARLY=1)
+    int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
+    int evict_early = 2;            // when that kernel starts (tuning: FC_EVICT_EARLY): 0 after the miss fill, under
+                                    // forward/backward; 1 right after the gather; 2 together with the miss fill
 
     // row geometry: VEC floats per lane access, LPR lanes per row
     int vec = 1, lpr = 1;

@@ -319,12 +319,14 @@ static int ensure_rbuf(fc_cache* c, int64_t n) {
 }
 
 // Evicted rows, default transmitter: gather into a device block on the caller's stream (so the slots can be
-// refilled at once); the block is stored into the mapped host table by a small kernel on the side stream.
-// Zero-copy stores that saturate the host link stall every other memory operation of the compute units they
-// run on (and delay reads in the other direction), so the store kernel is confined to a few workgroups
-// (c->evict_blocks) and, unless c->evict_early, starts only once the miss fill is done, running under the
-// forward / backward kernels.  Blocks before the last are stored at once because the one block buffer must be
-// free again for the next gather.
+// refilled at once); the block is stored into the mapped host table by a kernel on the side stream.
+// Measured on MI355X: zero-copy stores that saturate the host link stall the other memory operations of the
+// compute units they run on and starve reads in the other direction, so such a store must not run under small
+// latency-bound kernels (they wait for it to end) nor under the forward / backward kernels (they slow down
+// several-fold).  Default schedule (evict_early == 2): the store starts together with the miss fill, once all
+// index kernels are done, and the caller's stream waits for it right after the fill; the two then share the
+// link (the store finishes first, the fill catches up) and everything after runs undisturbed.
+// Blocks before the last are stored at once because the one block buffer must be free again for the next gather.
 static int store_block(fc_cache* c, int64_t off, int64_t rows) {
     FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
@@ -340,7 +342,7 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
         const int64_t rows = need - off < S ? need - off : S;
         if (off > 0) FC_HIP(hipStreamWaitEvent(c->stream, c->ev_evict_done, 0));   // block buffer is being read
         FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
-        if (off + rows >= need && !c->evict_early) { *last_off = off; *last_rows = rows; break; }
+        if (off + rows >= need && c->evict_early != 1) { *last_off = off; *last_rows = rows; break; }
         FC_TRY(store_block(c, off, rows));
     }
     return FC_OK;
@@ -451,10 +453,15 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
             k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
                                                       c->rank_slot);
         }
+        if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
+            FC_TRY(store_block(c, last_off, last_rows));
+            last_rows = -1;
+        }
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
     }
     if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
+    if (last_rows < 0) { FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0)); c->evict_pending = false; }
     if (n > 0) {
         ProfScope ps(c, P_SLOTS_OUT, st);
         k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);

@@ -12,7 +12,9 @@ template <> struct Vec<4> { using T = float4; };
 
 // dst[dst_idx ? dst_idx[j] : j] = src[src_idx ? src_idx[j] : j] for j in [0, rows); row length D floats.
 // lpr (power of two, <= 64) consecutive lanes own one row; a lane moves VEC floats per access.
-template <int VEC>
+// KIND only names the instantiation (profilers then tell the three uses apart): 0 evicted-row gather (HBM -> HBM
+// block), 1 evicted-row store (block -> host table), 2 miss fill (host table -> cache slots, or block -> slots).
+template <int VEC, int KIND>
 __global__ __launch_bounds__(256) void k_copy_rows(float* __restrict__ dst, const int32_t* __restrict__ dst_idx,
                                                    unsigned dst_rows, const float* __restrict__ src,
                                                    const int32_t* __restrict__ src_idx, unsigned src_rows, int rows,
@@ -60,11 +62,15 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
     int64_t blocks = cdiv(rows, gpb);
     if (blocks > max_blocks) blocks = max_blocks;
     ProfScope ps(c, prof_item, s);
-    switch (c->vec) {
-        case 4: k_copy_rows<4><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
-        case 2: k_copy_rows<2><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
-        default: k_copy_rows<1><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh); break;
-    }
+#define FC_LAUNCH_ROWS(V, K) \
+    k_copy_rows<V, K><<<(unsigned)blocks, 256, 0, s>>>(dst, dst_idx, (unsigned)dst_rows, src, src_idx, (unsigned)src_rows, (int)rows, c->D, sh)
+#define FC_LAUNCH_ROWS_V(K) \
+    switch (c->vec) { case 4: FC_LAUNCH_ROWS(4, K); break; case 2: FC_LAUNCH_ROWS(2, K); break; default: FC_LAUNCH_ROWS(1, K); break; }
+    if (prof_item == P_EVICT_GATHER) { FC_LAUNCH_ROWS_V(0) }
+    else if (prof_item == P_EVICT_STORE) { FC_LAUNCH_ROWS_V(1) }
+    else { FC_LAUNCH_ROWS_V(2) }
+#undef FC_LAUNCH_ROWS_V
+#undef FC_LAUNCH_ROWS
     FC_HIP(hipGetLastError());
     return FC_OK;
 }

@@ -70,7 +70,7 @@ enum {
 };
 
 /* Static module + dynamic module set-up (Sections 4.2, 4.3).
- *   num_rows, dim   table shape; fp32; dim >= 1.
+ *   num_rows, dim   table shape; fp32; 1 <= dim <= 1024.
  *   cache_rows      rows of the cached weight, 0 < cache_rows <= num_rows (the paper's cache ratio
  *                   times num_rows; 1.5% by default there).
  *   freq_rank_host  "idx_map": id -> row of the frequency-ordered table (0 = most frequent).

@@ -177,7 +177,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
-    if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || cache_rows <= 0 || cache_rows > num_rows ||
+    if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
         staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED)))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet

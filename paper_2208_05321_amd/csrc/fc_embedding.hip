@@ -244,83 +244,150 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
 // ---------------------------------------------------------------------------------------------------------
 // backward, step 2: chunked segmented reduction + SGD
 // ---------------------------------------------------------------------------------------------------------
-// pmeta[g] = {kind of the chunk's first run (0 complete / none pending, 1 = ends a run begun earlier,
-//             2 = whole chunk inside a longer run), 1 if the chunk's last run continues, slot of that run, 0}
+// A row-group owns BWD_CHUNK consecutive sorted lookups; a workgroup owns gpb such chunks in a row.
+// Runs (lookups of one slot) that lie inside a chunk are applied to the cached row at once.  Pieces of runs that
+// cross chunk borders meet in LDS and are joined in chunk order by the group where the run starts inside the
+// workgroup; only pieces of runs that cross WORKGROUP borders go to global memory (two rows per workgroup) and are
+// joined by k_bwd_fixup.  kinds of a chunk's / workgroup's first piece: 0 none, 1 = ends a run begun earlier,
+// 2 = lies wholly inside a longer run.
+struct BwdMeta { int first_kind, has_head, head_slot, pad; };
+
 template <int VEC>
 __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ keys, const int32_t* __restrict__ vals,
                                                     int n, int C, const float* __restrict__ grad, float* cache, int D,
                                                     int lpr_shift, float lr, float* __restrict__ part,
-                                                    int32_t* __restrict__ pmeta) {
+                                                    BwdMeta* __restrict__ bmeta) {
     using V = typename Vec<VEC>::T;
+    extern __shared__ __align__(16) unsigned char smem[];
     const int lpr = 1 << lpr_shift;
     const int gpb = blockDim.x >> lpr_shift;
     const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
     const int nv = D / VEC;
-    const int64_t g = (int64_t)blockIdx.x * gpb + gl;
-    const int64_t beg = g * BWD_CHUNK;
-    if (beg >= n) return;
-    const int end = (int)(beg + BWD_CHUNK < n ? beg + BWD_CHUNK : n);
-    V* __restrict__ pfirst = reinterpret_cast<V*>(part + (size_t)(g * 2) * D);
-    V* __restrict__ plast = reinterpret_cast<V*>(part + (size_t)(g * 2 + 1) * D);
+    // LDS: keys[gpb*CHUNK], vals[gpb*CHUNK], meta[gpb], pieces[gpb][2][D]
+    int* skeys = reinterpret_cast<int*>(smem);
+    int* svals = skeys + gpb * BWD_CHUNK;
+    BwdMeta* smeta = reinterpret_cast<BwdMeta*>(svals + gpb * BWD_CHUNK);
+    float* spiece = reinterpret_cast<float*>(smeta + gpb);
+    __shared__ BwdMeta blockmeta;
+
+    const int64_t blk0 = (int64_t)blockIdx.x * gpb * BWD_CHUNK;
+    for (int t = threadIdx.x; t < gpb * BWD_CHUNK; t += blockDim.x) {
+        const int64_t e = blk0 + t;
+        skeys[t] = e < n ? keys[e] : -1;
+        svals[t] = e < n ? vals[e] : 0;
+    }
+    if (threadIdx.x == 0) blockmeta = BwdMeta{0, 0, -1, 0};
+    __syncthreads();
+
+    const int64_t beg = blk0 + (int64_t)gl * BWD_CHUNK;
+    const int cnt = beg >= n ? 0 : (int)(beg + BWD_CHUNK <= n ? BWD_CHUNK : n - beg);
+    const int* mk = skeys + gl * BWD_CHUNK;
+    const int* mv = svals + gl * BWD_CHUNK;
+    V* __restrict__ pfirst = reinterpret_cast<V*>(spiece + (size_t)(gl * 2) * D);
+    V* __restrict__ plast = reinterpret_cast<V*>(spiece + (size_t)(gl * 2 + 1) * D);
     int first_kind = 0, has_head = 0, head_slot = -1;
-    for (int cidx = lane; cidx < nv; cidx += lpr) {
-        int cur = keys[beg];
-        bool open_left = beg > 0 && keys[beg - 1] == cur;
-        first_kind = 0; has_head = 0; head_slot = -1;
-        V acc = vzero(V());
-        for (int e = (int)beg; e < end; ++e) {
-            const int k = keys[e];
-            if (k != cur) {                       // run of `cur` ends inside the chunk
-                if (open_left) { pfirst[cidx] = acc; first_kind = 1; }
-                else if (cur < C) {
-                    V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
-                    row[cidx] = vsgd(row[cidx], acc, lr);
+    if (cnt > 0) {
+        const int prevk = gl > 0 ? mk[-1] : (beg > 0 ? keys[beg - 1] : -1);
+        const int nextk = beg + cnt < n ? (gl + 1 < gpb ? mk[BWD_CHUNK] : keys[beg + cnt]) : -2;
+        for (int cidx = lane; cidx < nv; cidx += lpr) {
+            int cur = mk[0];
+            bool open_left = prevk == cur;
+            first_kind = 0; has_head = 0; head_slot = -1;
+            V acc = vzero(V());
+            for (int e0 = 0; e0 < cnt; e0 += 8) {
+                V g[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)      // eight independent row loads in flight
+                    g[k] = e0 + k < cnt ? reinterpret_cast<const V*>(grad + (size_t)mv[e0 + k] * D)[cidx] : vzero(V());
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (e0 + k < cnt) {
+                        const int kk = mk[e0 + k];
+                        if (kk != cur) {              // run of `cur` ends inside the chunk
+                            if (open_left) { pfirst[cidx] = acc; first_kind = 1; }
+                            else if (cur < C) {
+                                V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
+                                row[cidx] = vsgd(row[cidx], acc, lr);
+                            }
+                            open_left = false;
+                            cur = kk;
+                            acc = vzero(V());
+                        }
+                        acc = vadd(acc, g[k]);
+                    }
                 }
-                open_left = false;
-                cur = k;
-                acc = vzero(V());
             }
-            acc = vadd(acc, reinterpret_cast<const V*>(grad + (size_t)vals[e] * D)[cidx]);
-        }
-        const bool open_right = end < n && keys[end] == cur;
-        if (open_left) { pfirst[cidx] = acc; first_kind = open_right ? 2 : 1; }
-        else if (open_right) { plast[cidx] = acc; has_head = 1; head_slot = cur; }
-        else if (cur < C) {
-            V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
-            row[cidx] = vsgd(row[cidx], acc, lr);
+            const bool open_right = nextk == cur;
+            if (open_left) { pfirst[cidx] = acc; first_kind = open_right ? 2 : 1; }
+            else if (open_right) { plast[cidx] = acc; has_head = 1; head_slot = cur; }
+            else if (cur < C) {
+                V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
+                row[cidx] = vsgd(row[cidx], acc, lr);
+            }
         }
     }
-    if (lane == 0) {
-        pmeta[g * 4 + 0] = first_kind;
-        pmeta[g * 4 + 1] = has_head;
-        pmeta[g * 4 + 2] = head_slot;
+    if (lane == 0) smeta[gl] = BwdMeta{first_kind, has_head, head_slot, 0};
+    __syncthreads();
+    // join the pieces inside the workgroup, in chunk order (chunks past the end of the batch have no pieces)
+    if (gl == 0 && first_kind != 0) {          // a run that entered from the previous workgroup
+        int kind = first_kind, j = 0;
+        while (kind == 2 && j + 1 < gpb && smeta[j + 1].first_kind != 0) { ++j; kind = smeta[j].first_kind; }
+        // chunks 0..j carry pieces of that run; kind says whether it ended (1) or leaves the workgroup (2)
+        V* __restrict__ out = reinterpret_cast<V*>(part + (size_t)(blockIdx.x * 2) * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) {
+            V acc = pfirst[cidx];
+            for (int q = 1; q <= j; ++q) acc = vadd(acc, reinterpret_cast<const V*>(spiece + (size_t)(q * 2) * D)[cidx]);
+            out[cidx] = acc;
+        }
+        if (lane == 0) blockmeta.first_kind = kind;
     }
+    if (has_head) {                             // a run that starts in this chunk and continues to the right
+        int j = gl, kind = 2;
+        while (kind == 2 && j + 1 < gpb && smeta[j + 1].first_kind != 0) { ++j; kind = smeta[j].first_kind; }
+        const bool closed = kind == 1;          // ended inside the workgroup
+        V* __restrict__ out = reinterpret_cast<V*>(part + (size_t)(blockIdx.x * 2 + 1) * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) {
+            V acc = plast[cidx];
+            for (int q = gl + 1; q <= j; ++q) acc = vadd(acc, reinterpret_cast<const V*>(spiece + (size_t)(q * 2) * D)[cidx]);
+            if (!closed) out[cidx] = acc;
+            else if (head_slot < C) {
+                V* row = reinterpret_cast<V*>(cache + (size_t)head_slot * D);
+                row[cidx] = vsgd(row[cidx], acc, lr);
+            }
+        }
+        if (!closed && lane == 0) { blockmeta.has_head = 1; blockmeta.head_slot = head_slot; }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) bmeta[blockIdx.x] = blockmeta;
 }
 
-// Runs that cross chunk borders: the chunk where the run starts adds the later chunks' pieces in order.
+// Runs that cross workgroup borders: the workgroup where the run starts adds the later workgroups' pieces in order.
 template <int VEC>
-__global__ __launch_bounds__(256) void k_bwd_fixup(int n, int C, float* cache, int D, int lpr_shift, float lr,
-                                                   const float* __restrict__ part, const int32_t* __restrict__ pmeta,
-                                                   int64_t groups) {
+__global__ __launch_bounds__(256) void k_bwd_fixup(int C, float* cache, int D, int lpr_shift, float lr,
+                                                   const float* __restrict__ part, const BwdMeta* __restrict__ bmeta,
+                                                   int nblocks) {
     using V = typename Vec<VEC>::T;
     const int lpr = 1 << lpr_shift;
     const int gpb = blockDim.x >> lpr_shift;
     const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
     const int nv = D / VEC;
-    const int64_t g = (int64_t)blockIdx.x * gpb + gl;
-    if (g >= groups || !pmeta[g * 4 + 1]) return;
-    const int slot = pmeta[g * 4 + 2];
+    const int b = blockIdx.x * gpb + gl;
+    if (b >= nblocks || !bmeta[b].has_head) return;
+    const int slot = bmeta[b].head_slot;
     if (slot >= C) return;
     for (int cidx = lane; cidx < nv; cidx += lpr) {
-        V acc = reinterpret_cast<const V*>(part + (size_t)(g * 2 + 1) * D)[cidx];
-        for (int64_t h = g + 1; h < groups; ++h) {
+        V acc = reinterpret_cast<const V*>(part + (size_t)(b * 2 + 1) * D)[cidx];
+        for (int h = b + 1; h < nblocks; ++h) {
             acc = vadd(acc, reinterpret_cast<const V*>(part + (size_t)(h * 2) * D)[cidx]);
-            if (pmeta[h * 4] != 2) break;
+            if (bmeta[h].first_kind != 2) break;
         }
         V* row = reinterpret_cast<V*>(cache + (size_t)slot * D);
         row[cidx] = vsgd(row[cidx], acc, lr);
     }
 }
+
+// threads per workgroup of the reduction: at most 64 chunks per workgroup
+static inline int bwd_threads(int lpr) { int t = 32 * lpr; if (t > 256) t = 256; if (t < 64) t = 64; return t; }
 
 static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
     if (n > c->sort_cap) {
@@ -347,7 +414,7 @@ static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
         c->part = nullptr; c->pmeta = nullptr; c->part_groups = 0;
         const int64_t cap = groups + groups / 4 + 64;
         FC_HIP(hipMalloc((void**)&c->part, (size_t)cap * 2 * c->D * 4));
-        FC_HIP(hipMalloc((void**)&c->pmeta, (size_t)cap * 4 * 4));
+        FC_HIP(hipMalloc((void**)&c->pmeta, (size_t)cap * sizeof(BwdMeta)));
         c->part_groups = cap;
     }
     return FC_OK;
@@ -367,8 +434,11 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     const int rb = (bits + passes - 1) / passes;
     const int radix = 1 << rb;
     const int64_t nblk = cdiv(n, RS_TILE);
-    const int64_t groups = cdiv(n, BWD_CHUNK);
-    FC_TRY(ensure_bwd(c, n, nblk, groups));
+    const int rthreads = bwd_threads(c->lpr);
+    const int rgpb = rthreads / c->lpr;                       // chunks per workgroup of the reduction
+    const int64_t rblocks = cdiv(n, (int64_t)rgpb * BWD_CHUNK);
+    const size_t lds = (size_t)rgpb * BWD_CHUNK * 8 + (size_t)rgpb * sizeof(BwdMeta) + (size_t)rgpb * 2 * c->D * 4;
+    FC_TRY(ensure_bwd(c, n, nblk, rblocks));
     const int32_t* kin = slots; const int32_t* vin = nullptr;
     int32_t* kout = c->keysA; int32_t* vout = c->valsA;
     for (int p = 0; p < passes; ++p) {
@@ -390,22 +460,23 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
         if (kout == c->keysA) { kout = c->keysB; vout = c->valsB; } else { kout = c->keysA; vout = c->valsA; }
     }
     const int sh = shift_of(c->lpr);
-    const int gpb = 256 >> sh;
-    const unsigned blocks = (unsigned)cdiv(groups, gpb);
     {
         ProfScope ps(c, P_BWD_REDUCE, st);
+        BwdMeta* bm = reinterpret_cast<BwdMeta*>(c->pmeta);
         switch (c->vec) {
-            case 4: k_bwd_reduce<4><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
-            case 2: k_bwd_reduce<2><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
-            default: k_bwd_reduce<1><<<blocks, 256, 0, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, c->pmeta); break;
+            case 4: k_bwd_reduce<4><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
+            case 2: k_bwd_reduce<2><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
+            default: k_bwd_reduce<1><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
         }
     }
     {
         ProfScope ps(c, P_BWD_FIXUP, st);
+        const BwdMeta* bm = reinterpret_cast<const BwdMeta*>(c->pmeta);
+        const unsigned fb = (unsigned)cdiv(rblocks, 256 >> sh);
         switch (c->vec) {
-            case 4: k_bwd_fixup<4><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
-            case 2: k_bwd_fixup<2><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
-            default: k_bwd_fixup<1><<<blocks, 256, 0, st>>>((int)n, (int)c->C, c->cache, c->D, sh, lr, c->part, c->pmeta, groups); break;
+            case 4: k_bwd_fixup<4><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
+            case 2: k_bwd_fixup<2><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
+            default: k_bwd_fixup<1><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
         }
     }
     FC_HIP(hipGetLastError());

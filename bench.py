@@ -36,6 +36,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--cache-ratio", type=float, default=0.015)
     ap.add_argument("--staged", action="store_true", help="use the block (gather / bulk copy / scatter) transmitter")
+    ap.add_argument("--dma-evict", action="store_true", help="evicted blocks leave by DMA, host threads scatter them")
     ap.add_argument("--staging-rows", type=int, default=0)
     ap.add_argument("--profile-steps", type=int, default=50, help="steps of the per-kernel HIP-event pass (0 = skip)")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
@@ -63,7 +64,7 @@ def main():
     stream = torch.cuda.Stream()
     torch.cuda.set_stream(stream)
     cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
-                      warm=False, staged=args.staged, stream=stream)
+                      warm=False, staged=args.staged, stream=stream, dma_evict=args.dma_evict)
     host = cache.host_weight()
     w.host_table(out=host)
     cache.warm()
@@ -220,7 +221,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_features} features in one {w.num_rows} x {w.dim} fp32 table, "
                                f"batch {w.samples} x {w.num_features} {'multi-hot' if w.multi_hot else 'one-hot'} ids, "
                                f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
-                   "transmitter": "staged-block" if args.staged else "direct",
+                   "transmitter": "staged-block" if args.staged else ("direct fill + DMA evict" if args.dma_evict else "direct"),
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
         "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5),

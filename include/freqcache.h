@@ -62,11 +62,18 @@ enum {
 /* cache_create flags */
 enum {
     FC_WARM = 1,            /* preload the cache_rows highest-frequency rows (Section 4.3, "cache warm-up") */
-    FC_TRANSMIT_STAGED = 2  /* move rows the way the paper's data transmitter does (Section 4.3):
+    FC_TRANSMIT_STAGED = 2, /* move rows the way the paper's data transmitter does (Section 4.3):
                                gather into a contiguous block on the source side, one bulk
                                hipMemcpyAsync over the host link, scatter on the target side.
                                Default (flag clear): kernels read / write the mapped pinned table
                                directly, one row-group of lanes per row.  Results are identical. */
+    FC_EVICT_DMA = 4        /* evicted rows only: the block leaves HBM by hipMemcpyAsync on the side stream (DMA
+                               engine, full duplex with the miss fill, no compute units involved) and library-owned
+                               host threads scatter it into the host table in the background (block transmitter of
+                               Section 4.3 for the device -> host direction).  Misses are still read by kernels.
+                               The host table is complete after cache_flush (or cache_check).  Number of threads:
+                               environment variable FC_SCATTER_THREADS (default 8).  Not with FC_TRANSMIT_STAGED.
+                               Results are identical. */
 };
 
 /* Static module + dynamic module set-up (Sections 4.2, 4.3).

@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     load_library,
     FC_WARM,
     FC_TRANSMIT_STAGED,
+    FC_EVICT_DMA,
     STAT_FIELDS,
 )

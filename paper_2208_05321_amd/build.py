@@ -8,9 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfreqcache.so")
-SOURCES = ["fc_api.hip", "fc_prepare.hip", "fc_rows.hip", "fc_embedding.hip"]
+SOURCES = ["fc_api.hip", "fc_prepare.hip", "fc_rows.hip", "fc_embedding.hip", "fc_worker.hip"]
 FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fopenmp",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fopenmp", "-pthread",
     "-ffp-contract=off",                                   # SGD step: rounded product, then subtract
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",

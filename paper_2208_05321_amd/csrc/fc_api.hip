@@ -66,6 +66,7 @@ __global__ void k_set_ctl(Ctl* ctl, int nfree) {
 
 static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
+    if (c->dma_evict) { pool_wait(c, pool_published(c)); c->blk_rows[0] = c->blk_rows[1] = 0; }
     const int64_t words = c->NB * RT_WORDS;
     k_iota_or_neg<<<1024, 256, 0, st>>>(c->rank_slot, c->N, warm ? c->C : 0);
     k_iota_or_neg<<<256, 256, 0, st>>>(c->slot_rank, c->C, warm ? c->C : 0);
@@ -85,6 +86,15 @@ static void destroy(fc_cache* c) {
     if (!c) return;
     (void)hipSetDevice(c->device);
     if (c->stream || c->side) (void)hipDeviceSynchronize();
+    pool_destroy(c);
+    if (c->dma_evict) c->vrank = nullptr;      // points into vrank_buf
+    for (int b = 0; b < 2; ++b) {
+        if (c->blk_pin[b]) (void)hipHostFree(c->blk_pin[b]);
+        if (c->vrank_pin[b]) (void)hipHostFree(c->vrank_pin[b]);
+        if (c->vrank_buf[b]) (void)hipFree(c->vrank_buf[b]);
+        if (c->ev_d2h[b]) (void)hipEventDestroy(c->ev_d2h[b]);
+    }
+    if (c->fill_src) (void)hipFree(c->fill_src);
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
                     (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
                     (void*)c->miss_ranks, (void*)c->vrank, (void*)c->vslot, (void*)c->fill_slots, (void*)c->rbuf,
@@ -145,11 +155,25 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipMalloc((void**)&c->vtake, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->voff, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->miss_ranks, (size_t)C * 4));
-    FC_HIP(hipMalloc((void**)&c->vrank, (size_t)C * 4));
+    c->dma_evict = (flags & FC_EVICT_DMA) != 0;
+    if (c->dma_evict) {
+        for (int b = 0; b < 2; ++b) {
+            FC_HIP(hipMalloc((void**)&c->vrank_buf[b], (size_t)C * 4));
+            if (hipHostMalloc((void**)&c->blk_pin[b], (size_t)staging_rows * D * 4, hipHostMallocDefault) != hipSuccess ||
+                hipHostMalloc((void**)&c->vrank_pin[b], (size_t)staging_rows * 4, hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError(); return FC_ERR_OOM_PINNED;
+            }
+            FC_HIP(hipEventCreateWithFlags(&c->ev_d2h[b], hipEventDisableTiming | hipEventBlockingSync));
+        }
+        FC_HIP(hipMalloc((void**)&c->fill_src, (size_t)C * 4));
+        c->vrank = c->vrank_buf[0];
+    } else {
+        FC_HIP(hipMalloc((void**)&c->vrank, (size_t)C * 4));
+    }
     FC_HIP(hipMalloc((void**)&c->vslot, (size_t)C * 4));
     FC_HIP(hipMalloc((void**)&c->fill_slots, (size_t)C * 4));
     FC_HIP(hipMalloc((void**)&c->ctl, sizeof(Ctl)));
-    FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4));
+    FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4 * (c->dma_evict ? 2 : 1)));
     if (hipHostMalloc((void**)&c->hctl, sizeof(HostCtl), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_OOM_PINNED; }
     memset(c->hctl, 0, sizeof(HostCtl));
     if (flags & FC_TRANSMIT_STAGED) {
@@ -163,6 +187,11 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
+    if (c->dma_evict) {
+        int threads = 8;
+        if (const char* e = getenv("FC_SCATTER_THREADS")) { const int v = atoi(e); if (v >= 1 && v <= 64) threads = v; }
+        FC_TRY(pool_create(c, threads));
+    }
     return reset_state(c, (flags & FC_WARM) != 0);
 }
 
@@ -178,7 +207,8 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
-        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED)))
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA)) ||
+        ((flags & FC_TRANSMIT_STAGED) && (flags & FC_EVICT_DMA)))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
     {   // idx_map must be a permutation: the host table is the original table re-ordered (Section 4.2)
@@ -229,6 +259,7 @@ int cache_flush(fc_cache* c) {
     FC_HIP(hipSetDevice(c->device));
     FC_HIP(hipStreamSynchronize(c->side));      // pending evicted rows first: flush must not be overtaken
     c->evict_pending = false;
+    FC_TRY(dma_quiesce(c));
     if (c->flags & FC_TRANSMIT_STAGED) {
         // the cached weight is contiguous: bulk-copy slot ranges, scatter the resident ones on the host
         std::vector<int32_t> sr((size_t)c->C);
@@ -258,6 +289,8 @@ int cache_check(fc_cache* c) {
     FC_HIP(hipSetDevice(c->device));
     FC_HIP(hipStreamSynchronize(c->stream));
     FC_HIP(hipStreamSynchronize(c->side));
+    FC_TRY(dma_quiesce(c));
+    FC_HIP(hipStreamSynchronize(c->stream));
     Ctl h;
     FC_HIP(hipMemcpy(&h, c->ctl, sizeof(Ctl), hipMemcpyDeviceToHost));
     if (h.async_flags) {
@@ -284,7 +317,11 @@ int cache_copy_state(fc_cache* c, int32_t* slot_rank_host, int32_t* rank_slot_ho
     FC_HIP(hipSetDevice(c->device));
     FC_HIP(hipStreamSynchronize(c->stream));
     if (slot_rank_host) FC_HIP(hipMemcpy(slot_rank_host, c->slot_rank, (size_t)c->C * 4, hipMemcpyDeviceToHost));
-    if (rank_slot_host) FC_HIP(hipMemcpy(rank_slot_host, c->rank_slot, (size_t)c->N * 4, hipMemcpyDeviceToHost));
+    if (rank_slot_host) {
+        FC_HIP(hipMemcpy(rank_slot_host, c->rank_slot, (size_t)c->N * 4, hipMemcpyDeviceToHost));
+        if (c->dma_evict)      // "in transit" is an internal shade of "not resident"
+            for (int64_t r = 0; r < c->N; ++r) if (rank_slot_host[r] < -1) rank_slot_host[r] = -1;
+    }
     return FC_OK;
 }
 

@@ -48,6 +48,8 @@ enum ProfItem {
 
 struct ProfSpan { int item; hipEvent_t a, b; };
 
+struct ScatterPool;   // host threads that scatter evicted-row blocks into the host table (fc_worker.hip)
+
 }  // namespace fc
 
 struct fc_cache {
@@ -92,6 +94,20 @@ struct fc_cache {
     float* stage_dev2 = nullptr;    // staged mode: H2D block
     float* stage_pin = nullptr;     // staged mode: pinned block (both directions)
     int32_t* list_pin = nullptr;    // staged mode: pinned copies of miss / victim rank lists [2*C]
+
+    // DMA evict transmitter (FC_EVICT_DMA): evicted-row blocks leave HBM by hipMemcpyAsync on the side stream and
+    // are scattered into the host table by worker threads; two blocks in flight.  While a row's newest copy is
+    // still on its way, rank_slot[rank] = -2 - (block * staging_rows + row in block) ("in transit") and a miss
+    // on it is served from the device-side block instead of the host table.
+    bool dma_evict = false;
+    fc::ScatterPool* pool = nullptr;
+    float* blk_pin[2] = {nullptr, nullptr};       // pinned landing blocks
+    int32_t* vrank_pin[2] = {nullptr, nullptr};   // pinned copies of the evicted ranks
+    int32_t* vrank_buf[2] = {nullptr, nullptr};   // device lists of the evicted ranks, one per block
+    int64_t blk_rows[2] = {0, 0};                 // rows whose transit marks are still set, per block
+    hipEvent_t ev_d2h[2] = {nullptr, nullptr};
+    int32_t* fill_src = nullptr;                  // [C] where each missing row is read from (-1 host, <= -2 transit)
+    uint64_t dma_seq = 0;                         // blocks handed to the pool so far
 
     float* host = nullptr;          // pinned, rank-ordered table
     float* host_dev = nullptr;      // its device-side address
@@ -148,6 +164,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // entry points implemented across the sources
 int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots);
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
+int dma_quiesce(fc_cache* c);
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
              const float* grad, float lr);
 
@@ -157,6 +174,15 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
                      const float* src, const int32_t* src_idx, int64_t src_rows, int64_t rows, int max_blocks);
 // host[slot_rank[s]] = cache[s] for every resident slot, written straight into the mapped host table.
 int launch_flush_rows(fc_cache* c, hipStream_t s);
+// miss fill that honours transit marks: row j comes from the host table or from a device-side evicted-row block
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows);
+
+// scatter pool (fc_worker.hip)
+int pool_create(fc_cache* c, int threads);
+void pool_destroy(fc_cache* c);
+void pool_publish(fc_cache* c, int buf, int64_t rows);   // block `buf` holds `rows` rows once ev_d2h[buf] fires
+void pool_wait(fc_cache* c, uint64_t seq);               // until block number `seq` (1-based) is in the host table
+uint64_t pool_published(fc_cache* c);
 
 // ---- device helpers ----
 template <int NT>

@@ -184,7 +184,8 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
                                                           const int32_t* __restrict__ voff,
                                                           int32_t* __restrict__ miss_ranks, int32_t* __restrict__ vrank,
                                                           int32_t* __restrict__ vslot, int32_t* rank_slot,
-                                                          int32_t* slot_rank, int C) {
+                                                          int32_t* slot_rank, int C, int transit_base,
+                                                          int transit_rows) {
     __shared__ int lds[RT_THREADS / 64];
     const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
     const uint4 u4 = ubits4[idx];
@@ -224,6 +225,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
     if (vt > 0) {
         int totc;
         const int pc = block_excl_scan<RT_THREADS>(cc, totc, lds);
+        const bool transit = transit_base >= 0 && ctl->need <= transit_rows;
         const int skip = totc - vt;          // the lowest `skip` evictable ranks of the threshold tile stay
         const int o0 = voff[blockIdx.x];
         int q = pc;
@@ -239,7 +241,9 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
                         const int j = o0 + q - skip;
                         vrank[j] = rank;
                         vslot[j] = slot;
-                        rank_slot[rank] = -1;
+                        // not resident any more; with the DMA evict transmitter the newest copy of the row is
+                        // "in transit" in row j of an evicted-row block until the host threads have stored it
+                        rank_slot[rank] = transit ? -2 - (transit_base + j) : -1;
                         if ((unsigned)slot < (unsigned)C) slot_rank[slot] = -1;   // always true: the maps are inverse
                         vw[k] |= 1u << bit;
                     }
@@ -279,7 +283,8 @@ __global__ __launch_bounds__(FREE_TILE) void k_free_count(const int32_t* __restr
 
 __global__ __launch_bounds__(FREE_TILE) void k_free_assign(int32_t* slot_rank, int C, const int32_t* __restrict__ tcount,
                                                            int M, const int32_t* __restrict__ miss_ranks,
-                                                           int32_t* __restrict__ fill_slots, int32_t* rank_slot) {
+                                                           int32_t* __restrict__ fill_slots, int32_t* rank_slot,
+                                                           int32_t* __restrict__ fill_src) {
     __shared__ int lds[FREE_TILE / 64];
     int part = 0;
     for (int g = threadIdx.x; g < (int)blockIdx.x; g += FREE_TILE) part += tcount[g];
@@ -294,7 +299,19 @@ __global__ __launch_bounds__(FREE_TILE) void k_free_assign(int32_t* slot_rank, i
         const int r = miss_ranks[j];
         fill_slots[j] = s;
         slot_rank[s] = r;
+        if (fill_src) fill_src[j] = rank_slot[r];     // -1: host table; <= -2: evicted-row block (in transit)
         rank_slot[r] = s;
+    }
+}
+
+// DMA evict transmitter: the host threads have stored block `base / staging_rows`; rows still marked as in transit
+// in that block are plain "not resident" again (a row re-fetched or re-evicted meanwhile carries another value).
+__global__ __launch_bounds__(256) void k_clear_transit(const int32_t* __restrict__ ranks, int count, int base,
+                                                       int32_t* rank_slot) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < count) {
+        const int r = ranks[j];
+        if (rank_slot[r] == -2 - (base + j)) rank_slot[r] = -1;
     }
 }
 
@@ -348,6 +365,40 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
     return FC_OK;
 }
 
+// DMA evict transmitter: wait until every handed-over block is in the host table and drop all transit marks
+// (afterwards the host table alone is current for every non-resident row, and both blocks are free).
+int dma_quiesce(fc_cache* c) {
+    if (!c->dma_evict) return FC_OK;
+    pool_wait(c, pool_published(c));
+    for (int b = 0; b < 2; ++b) {
+        if (c->blk_rows[b] > 0) {
+            k_clear_transit<<<(unsigned)cdiv(c->blk_rows[b], 256), 256, 0, c->stream>>>(c->vrank_buf[b], (int)c->blk_rows[b],
+                                                                                       (int)(b * c->staging_rows), c->rank_slot);
+            c->blk_rows[b] = 0;
+        }
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+// DMA evict transmitter: gather into block `buf`, hand the block and its rank list to the DMA engine on the side
+// stream, and let the host threads scatter it once it has landed.  Nothing on the caller's stream waits for it.
+static int evict_dma(fc_cache* c, int64_t need, int buf) {
+    float* blk = c->stage_dev + (size_t)buf * c->staging_rows * c->D;
+    FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, blk, nullptr, c->staging_rows, c->cache, c->vslot, c->C, need, 1 << 20));
+    FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
+    FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
+    {
+        ProfScope ps(c, P_D2H_BLOCK, c->side);
+        FC_HIP(hipMemcpyAsync(c->vrank_pin[buf], c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, c->side));
+        FC_HIP(hipMemcpyAsync(c->blk_pin[buf], blk, (size_t)need * c->D * 4, hipMemcpyDeviceToHost, c->side));
+    }
+    FC_HIP(hipEventRecord(c->ev_d2h[buf], c->side));
+    c->blk_rows[buf] = need;
+    pool_publish(c, buf, need);
+    return FC_OK;
+}
+
 // The paper's transmitter: block on the source side -> one bulk copy -> scatter on the target side.
 static int evict_staged(fc_cache* c, int64_t need, const int32_t* vrank_host) {
     const int64_t S = c->staging_rows;
@@ -392,6 +443,20 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     hipStream_t st = c->stream;
+    int transit_base = -1, buf = 0;
+    if (c->dma_evict) {
+        // the block this call may fill was handed over two blocks ago: its rows must be in the host table by now
+        const uint64_t seq = pool_published(c) + 1;
+        buf = (int)(seq & 1);
+        if (seq > 2) pool_wait(c, seq - 2);
+        if (c->blk_rows[buf] > 0) {
+            k_clear_transit<<<(unsigned)cdiv(c->blk_rows[buf], 256), 256, 0, st>>>(c->vrank_buf[buf], (int)c->blk_rows[buf],
+                                                                                (int)(buf * c->staging_rows), c->rank_slot);
+            c->blk_rows[buf] = 0;
+        }
+        c->vrank = c->vrank_buf[buf];
+        transit_base = (int)(buf * c->staging_rows);
+    }
     const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
     int64_t nmark = cdiv(work, 4 * MARK_THREADS);
     if (nmark > MARK_MAX_BLOCKS) nmark = MARK_MAX_BLOCKS;
@@ -422,7 +487,7 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     {
         ProfScope ps(c, P_RANK_EMIT, st);
         k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, c->ctl, c->moff, c->vtake, c->voff,
-                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C);
+                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C, transit_base, (int)c->staging_rows);
     }
     FC_HIP(hipGetLastError());
     FC_HIP(hipEventSynchronize(c->ev_plan));
@@ -441,7 +506,16 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
         FC_HIP(hipStreamSynchronize(st));
     }
     int64_t last_off = 0, last_rows = 0;
-    if (need > 0) FC_TRY(staged ? evict_staged(c, need, c->list_pin + c->C) : evict_direct(c, need, &last_off, &last_rows));
+    if (need > 0) {
+        if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
+        else if (c->dma_evict && need <= c->staging_rows) FC_TRY(evict_dma(c, need, buf));
+        else {
+            // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
+            // block buffer is reused from its start, so nothing may be in transit in it any more
+            FC_TRY(dma_quiesce(c));
+            FC_TRY(evict_direct(c, need, &last_off, &last_rows));
+        }
+    }
     if (M > 0) {
         {
             const unsigned tiles = (unsigned)cdiv(c->C, FREE_TILE);
@@ -451,13 +525,14 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
             }
             ProfScope ps(c, P_FREE_PICK, st);
             k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
-                                                      c->rank_slot);
+                                                      c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
         if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
             FC_TRY(store_block(c, last_off, last_rows));
             last_rows = -1;
         }
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
+        else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
     }
     if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));

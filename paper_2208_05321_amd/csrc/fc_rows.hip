@@ -52,6 +52,39 @@ __global__ __launch_bounds__(256) void k_flush_rows(float* __restrict__ host, co
     }
 }
 
+// Miss fill of the DMA evict transmitter: row j goes to slot fill_slots[j]; it comes from the host table, or, if
+// its newest copy is still in transit (fill_src[j] <= -2), from the evicted-row block that holds it.
+template <int VEC>
+__global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, const int32_t* __restrict__ fill_slots,
+                                                   unsigned C, const float* __restrict__ host,
+                                                   const int32_t* __restrict__ miss_ranks, unsigned N,
+                                                   const float* __restrict__ blocks, const int32_t* __restrict__ fill_src,
+                                                   unsigned block_rows, int rows, int D, int lpr_shift) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    for (int j = blockIdx.x * gpb + gl; j < rows; j += gridDim.x * gpb) {
+        const int di = fill_slots[j];
+        const int code = fill_src[j];
+        const float* srow;
+        if (code <= -2) {
+            const unsigned k = (unsigned)(-2 - code);
+            if (k >= block_rows) continue;
+            srow = blocks + (size_t)k * D;
+        } else {
+            const int r = miss_ranks[j];
+            if ((unsigned)r >= N) continue;
+            srow = host + (size_t)r * D;
+        }
+        if ((unsigned)di >= C) continue;
+        const V* __restrict__ s = reinterpret_cast<const V*>(srow);
+        V* __restrict__ d = reinterpret_cast<V*>(cache + (size_t)di * D);
+        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = s[cidx];
+    }
+}
+
 static inline int shift_of(int lpr) { int s = 0; while ((1 << s) < lpr) ++s; return s; }
 
 int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, const int32_t* dst_idx, int64_t dst_rows,
@@ -71,6 +104,22 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
     else { FC_LAUNCH_ROWS_V(2) }
 #undef FC_LAUNCH_ROWS_V
 #undef FC_LAUNCH_ROWS
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows) {
+    if (rows <= 0) return FC_OK;
+    const int sh = shift_of(c->lpr);
+    const int gpb = 256 >> sh;
+    int64_t blocks = cdiv(rows, gpb);
+    if (blocks > (1 << 20)) blocks = 1 << 20;
+    ProfScope ps(c, P_MISS_FILL, s);
+#define FC_FILL(V) \
+    k_fill_rows<V><<<(unsigned)blocks, 256, 0, s>>>(c->cache, c->fill_slots, (unsigned)c->C, c->host_dev, c->miss_ranks, (unsigned)c->N, \
+                                                    c->stage_dev, c->fill_src, (unsigned)(2 * c->staging_rows), (int)rows, c->D, sh)
+    switch (c->vec) { case 4: FC_FILL(4); break; case 2: FC_FILL(2); break; default: FC_FILL(1); break; }
+#undef FC_FILL
     FC_HIP(hipGetLastError());
     return FC_OK;
 }

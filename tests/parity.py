@@ -55,7 +55,8 @@ def compare_prepare(gpu, orc, slots_gpu, slots_orc, t, deep=True):
         assert np.array_equal(rs, orc.rank_slot), f"batch {t}: rank->slot map"
 
 
-def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_every=1, values_every=1, log=None):
+def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_every=1, values_every=1, log=None,
+               dma_evict=False):
     """Drive the GPU library and the oracle over the first `num_batches` batches of workload `w`."""
     import torch
     from oracle import Oracle
@@ -63,7 +64,7 @@ def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_eve
 
     dev = torch.device("cuda:0")
     gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, staged=staged)
+                    warm=False, staged=staged, dma_evict=dma_evict)
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()

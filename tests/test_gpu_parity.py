@@ -61,3 +61,43 @@ def test_staged_block_transmitter(torch_cuda, staging_rows):
     w = make_workload("c2", scale=0.02, cache_ratio=0.04)
     run_parity(w, 6, warm=True, staged=True, staging_rows=staging_rows)
     run_parity(w, 4, warm=False, staged=True, staging_rows=staging_rows)
+
+
+@pytest.mark.parametrize("staging_rows", [0, 3000, 7])
+def test_dma_evict_transmitter(torch_cuda, staging_rows):
+    """Evicted blocks leave by DMA and are scattered by host threads; rows whose newest copy is still in transit are
+    served from the device-side block.  staging_rows 3000: some batches fit one block, some fall back to the
+    kernel store; 7: every batch falls back.  Results are identical to the oracle in all cases."""
+    w = make_workload("c2", scale=0.1, cache_ratio=0.015)
+    tot = run_parity(w, 14, warm=True, dma_evict=True, staging_rows=staging_rows, deep_every=2, values_every=2)
+    assert tot["evict"] > 0
+    run_parity(w, 6, warm=False, dma_evict=True, staging_rows=staging_rows)
+
+
+def test_dma_evict_rows_come_back_quickly(torch_cuda):
+    """A tiny cache thrashed by alternating id sets: rows evicted in one batch are missed in the next (served from
+    the in-transit block) and evicted again two batches later."""
+    import torch
+    from tests.tiny_workload import TinyWorkload
+    from tests.parity import compare_prepare
+    from tests.test_gpu_edge import make_pair
+    w = TinyWorkload(num_rows=600, dim=64, cache_rows=40, seed=11, multi_hot=False)
+    gpu, orc = make_pair(w, warm=True, dma_evict=True)
+    dev = torch.device("cuda:0")
+    sets = [np.arange(0, 30), np.arange(30, 60), np.arange(15, 45), np.arange(100, 130)]
+    for t in range(40):
+        ids = sets[t % len(sets) if t % 7 else 0].astype(np.int64)
+        off = np.arange(len(ids) + 1, dtype=np.int64)
+        g = np.random.default_rng(t).standard_normal((len(ids), w.dim)).astype(np.float32)
+        so = orc.prepare(ids, off)
+        sd = gpu.prepare(torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev))
+        compare_prepare(gpu, orc, sd.cpu().numpy(), so, t)
+        od = gpu.embedding_bag_fwd(sd, torch.from_numpy(off).to(dev))
+        assert_close(od.cpu().numpy(), orc.embedding_bag_fwd(so, off), f"fwd {t}")
+        gpu.embedding_bag_bwd_sgd(sd, torch.from_numpy(off).to(dev), torch.from_numpy(g).to(dev), 0.05)
+        orc.embedding_bag_bwd_sgd(so, off, g, 0.05)
+    gpu.check()
+    gpu.flush()
+    orc.flush()
+    assert_close(gpu.host_weight(), orc.host, "host table")
+    gpu.close()

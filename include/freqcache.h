@@ -67,13 +67,17 @@ enum {
                                hipMemcpyAsync over the host link, scatter on the target side.
                                Default (flag clear): kernels read / write the mapped pinned table
                                directly, one row-group of lanes per row.  Results are identical. */
-    FC_EVICT_DMA = 4        /* evicted rows only: the block leaves HBM by hipMemcpyAsync on the side stream (DMA
+    FC_EVICT_DMA = 4,       /* evicted rows only: the block leaves HBM by hipMemcpyAsync on the side stream (DMA
                                engine, full duplex with the miss fill, no compute units involved) and library-owned
                                host threads scatter it into the host table in the background (block transmitter of
                                Section 4.3 for the device -> host direction).  Misses are still read by kernels.
                                The host table is complete after cache_flush (or cache_check).  Number of threads:
                                environment variable FC_SCATTER_THREADS (default 8).  Not with FC_TRANSMIT_STAGED.
                                Results are identical. */
+    FC_NO_PRESORT = 8       /* By default cache_prepare also starts, on a library-owned stream, the sort of the
+                               batch's (slot, bag) pairs that embedding_bag_bwd_sgd needs, so that it overlaps the
+                               miss fill; it reads slots_dev and offsets_dev until it is done.  Set this flag when
+                               no backward pass follows (inference) or those buffers are reused at once. */
 };
 
 /* Static module + dynamic module set-up (Sections 4.2, 4.3).
@@ -92,7 +96,7 @@ enum {
  *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3, "the memory
  *                   footprint of the data transmitter is strictly limited"); larger transfers are
  *                   done in several rounds.  0 = default (min(cache_rows, 131072)).
- *   flags           FC_WARM | FC_TRANSMIT_STAGED.
+ *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.
  * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous. */

@@ -31,6 +31,7 @@ ProfScope::~ProfScope() {
 void prof_collect(fc_cache* c) {
     (void)hipStreamSynchronize(c->stream);
     (void)hipStreamSynchronize(c->side);
+    if (c->aux) (void)hipStreamSynchronize(c->aux);
     for (const ProfSpan& sp : c->spans) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) { c->prof_ms[sp.item] += ms; c->prof_n[sp.item] += 1; }
@@ -105,8 +106,9 @@ static void destroy(fc_cache* c) {
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_sorted}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
+    if (c->aux) (void)hipStreamDestroy(c->aux);
     delete c;
 }
 
@@ -184,7 +186,9 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
         }
     }
     FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp})
+    FC_HIP(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
+    c->presort = (flags & FC_NO_PRESORT) == 0;
+    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
     if (c->dma_evict) {
@@ -207,7 +211,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
-        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA)) ||
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT)) ||
         ((flags & FC_TRANSMIT_STAGED) && (flags & FC_EVICT_DMA)))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
@@ -287,6 +291,7 @@ int cache_flush(fc_cache* c) {
 int cache_check(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->aux));
     FC_HIP(hipStreamSynchronize(c->stream));
     FC_HIP(hipStreamSynchronize(c->side));
     FC_TRY(dma_quiesce(c));

@@ -420,25 +420,15 @@ static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
     return FC_OK;
 }
 
-int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
-             const float* grad, float lr) {
-    const int64_t LIM = ((int64_t)1 << 31) - 65536;
-    if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!slots || !grad || num_bags == 0)))
-        return FC_ERR_INVALID_ARG;
-    if (n == 0) return FC_OK;
-    FC_HIP(hipSetDevice(c->device));
-    hipStream_t st = c->stream;
+// Stable sort of the batch's (slot, bag) pairs by slot on stream `st`; *kres / *vres receive the sorted arrays.
+static int sort_pairs(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t n, const int64_t* offsets,
+                      int64_t num_bags, const int32_t** kres, const int32_t** vres) {
     int bits = 1;
     while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
     const int passes = (bits + RS_MAX_BITS - 1) / RS_MAX_BITS;
     const int rb = (bits + passes - 1) / passes;
     const int radix = 1 << rb;
     const int64_t nblk = cdiv(n, RS_TILE);
-    const int rthreads = bwd_threads(c->lpr);
-    const int rgpb = rthreads / c->lpr;                       // chunks per workgroup of the reduction
-    const int64_t rblocks = cdiv(n, (int64_t)rgpb * BWD_CHUNK);
-    const size_t lds = (size_t)rgpb * BWD_CHUNK * 8 + (size_t)rgpb * sizeof(BwdMeta) + (size_t)rgpb * 2 * c->D * 4;
-    FC_TRY(ensure_bwd(c, n, nblk, rblocks));
     const int32_t* kin = slots; const int32_t* vin = nullptr;
     int32_t* kout = c->keysA; int32_t* vout = c->valsA;
     for (int p = 0; p < passes; ++p) {
@@ -459,6 +449,55 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
         kin = kout; vin = vout;
         if (kout == c->keysA) { kout = c->keysB; vout = c->valsB; } else { kout = c->keysA; vout = c->valsA; }
     }
+    FC_HIP(hipGetLastError());
+    *kres = kin; *vres = vin;
+    return FC_OK;
+}
+
+static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int64_t* rblocks, size_t* lds) {
+    *rthreads = bwd_threads(c->lpr);
+    const int rgpb = *rthreads / c->lpr;                      // chunks per workgroup of the reduction
+    *rblocks = cdiv(n, (int64_t)rgpb * BWD_CHUNK);
+    *lds = (size_t)rgpb * BWD_CHUNK * 8 + (size_t)rgpb * sizeof(BwdMeta) + (size_t)rgpb * 2 * c->D * 4;
+}
+
+// Called by cache_prepare once the slots of the batch are on their way: the sort needs nothing but the slots and
+// the bag offsets, so it runs on the auxiliary stream while the missing rows are still crossing the host link.
+int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags) {
+    c->ps_valid = false;
+    if (!c->presort || n <= 0 || num_bags <= 0) return FC_OK;
+    int rthreads; int64_t rblocks; size_t lds;
+    bwd_geometry(c, n, &rthreads, &rblocks, &lds);
+    FC_TRY(ensure_bwd(c, n, cdiv(n, RS_TILE), rblocks));
+    FC_HIP(hipEventRecord(c->ev_slots, c->stream));
+    FC_HIP(hipStreamWaitEvent(c->aux, c->ev_slots, 0));
+    FC_TRY(sort_pairs(c, c->aux, slots, n, offsets, num_bags, &c->ps_keys, &c->ps_vals));
+    FC_HIP(hipEventRecord(c->ev_sorted, c->aux));
+    c->ps_slots = slots; c->ps_n = n; c->ps_offsets = offsets; c->ps_bags = num_bags;
+    c->ps_valid = true;
+    return FC_OK;
+}
+
+int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+             const float* grad, float lr) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!slots || !grad || num_bags == 0)))
+        return FC_ERR_INVALID_ARG;
+    if (n == 0) return FC_OK;
+    FC_HIP(hipSetDevice(c->device));
+    hipStream_t st = c->stream;
+    int rthreads; int64_t rblocks; size_t lds;
+    bwd_geometry(c, n, &rthreads, &rblocks, &lds);
+    const int32_t* kin; const int32_t* vin;
+    if (c->ps_valid && c->ps_slots == slots && c->ps_n == n && c->ps_offsets == offsets && c->ps_bags == num_bags) {
+        FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));      // sorted ahead of time by cache_prepare
+        kin = c->ps_keys; vin = c->ps_vals;
+    } else {
+        if (c->ps_valid) FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));   // the scratch buffers are shared
+        FC_TRY(ensure_bwd(c, n, cdiv(n, RS_TILE), rblocks));
+        FC_TRY(sort_pairs(c, st, slots, n, offsets, num_bags, &kin, &vin));
+    }
+    c->ps_valid = false;
     const int sh = shift_of(c->lpr);
     {
         ProfScope ps(c, P_BWD_REDUCE, st);

@@ -121,6 +121,15 @@ struct fc_cache {
     int32_t* pmeta = nullptr;       // [groups][4]
     int64_t part_groups = 0;
 
+    // sort of the (slot, bag) pairs started by cache_prepare on the auxiliary stream
+    bool presort = true;            // FC_NO_PRESORT clears it
+    hipStream_t aux = nullptr;
+    hipEvent_t ev_slots = nullptr, ev_sorted = nullptr;
+    bool ps_valid = false;
+    const int32_t* ps_slots = nullptr; const int64_t* ps_offsets = nullptr;
+    int64_t ps_n = 0, ps_bags = 0;
+    const int32_t *ps_keys = nullptr, *ps_vals = nullptr;
+
     // last prepare
     fc_stats last = {};
     bool have_lists = false;
@@ -165,6 +174,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots);
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
 int dma_quiesce(fc_cache* c);
+int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags);
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
              const float* grad, float lr);
 

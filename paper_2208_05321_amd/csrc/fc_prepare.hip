@@ -443,6 +443,10 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     hipStream_t st = c->stream;
+    if (c->ps_valid) {                       // a sort nobody used: its scratch buffers must be free before the next one
+        FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));
+        c->ps_valid = false;
+    }
     int transit_base = -1, buf = 0;
     if (c->dma_evict) {
         // the block this call may fill was handed over two blocks ago: its rows must be in the host table by now
@@ -527,6 +531,15 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
             k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
                                                       c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
+        // every row of the batch has its slot now: write the slots out and start sorting them for the backward
+        // pass on the auxiliary stream, while the missing rows cross the host link
+        if (n > 0) {
+            {
+                ProfScope ps(c, P_SLOTS_OUT, st);
+                k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
+            }
+            (void)presort_impl(c, slots, n, offsets, num_bags);   // on failure the backward pass sorts (and reports) itself
+        }
         if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
             FC_TRY(store_block(c, last_off, last_rows));
             last_rows = -1;
@@ -535,12 +548,15 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
         else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
     }
+    if (M == 0 && n > 0) {
+        {
+            ProfScope ps(c, P_SLOTS_OUT, st);
+            k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
+        }
+        (void)presort_impl(c, slots, n, offsets, num_bags);
+    }
     if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
     if (last_rows < 0) { FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0)); c->evict_pending = false; }
-    if (n > 0) {
-        ProfScope ps(c, P_SLOTS_OUT, st);
-        k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
-    }
     FC_HIP(hipGetLastError());
     c->last.n_ids = n;
     c->last.n_unique = h.n_unique;

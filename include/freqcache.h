@@ -95,7 +95,7 @@ enum {
  *                   the store of record: evictions and cache_flush write into it.
  *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3, "the memory
  *                   footprint of the data transmitter is strictly limited"); larger transfers are
- *                   done in several rounds.  0 = default (min(cache_rows, 131072)).
+ *                   done in several rounds.  0 = default (min(cache_rows, 524288)).
  *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.

@@ -121,7 +121,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     const int nv = D / c->vec;
     c->lpr = 1;
     while (c->lpr < nv && c->lpr < 64) c->lpr <<= 1;
-    if (staging_rows <= 0) staging_rows = C < 131072 ? C : 131072;
+    if (staging_rows <= 0) staging_rows = C < 524288 ? C : 524288;
     if (staging_rows > C) staging_rows = C;
     c->staging_rows = staging_rows;
     if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }

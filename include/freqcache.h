@@ -167,6 +167,27 @@ int cache_copy_rows(fc_cache* c, float* rows_host);
 float* cache_host_weight(fc_cache* c);
 const char* cache_strerror(int code);
 
+/* ---- static module (Section 4.2): id frequency statistics -> freq_rank, built on the GPU ---- */
+typedef struct fc_freq fc_freq; /* opaque accumulator of per-id occurrence counts */
+
+/* Zeroed counters for ids in [0, num_rows) on the current device; work is enqueued on hip_stream. */
+int freq_create(int64_t num_rows, void* hip_stream, fc_freq** out);
+/* counts[id] += 1 for each of the n ids (int64, device memory): one scan step over the dataset, or over a sample of
+ * it when the dataset is too large (Section 4.2).  Asynchronous; ids outside [0, num_rows) are skipped and make
+ * freq_build fail with FC_ERR_ID_OUT_OF_RANGE. */
+int freq_add(fc_freq* f, const int64_t* ids_dev, int64_t n);
+/* Order the rows from high to low occurrence count, equal counts by lower id:
+ *   freq_rank_host[id] = position of id in that order (the idx_map cache_create takes), int32[num_rows];
+ *   inv_rank_host[r]   = id at position r, int32[num_rows];   counts_host[id] = its count.  Each may be NULL.
+ * Synchronous; the counters stay valid (more freq_add / freq_build calls may follow). */
+int freq_build(fc_freq* f, int32_t* freq_rank_host, int32_t* inv_rank_host, int32_t* counts_host);
+int freq_destroy(fc_freq* f);
+/* Re-order an embedding table by frequency: dst[r, :] = src[inv_rank[r], :] for r in [0, num_rows), fp32 rows of `dim`.
+ * src_pinned and dst_pinned are distinct page-locked, GPU-mapped host buffers (the rows cross the host link twice);
+ * inv_rank_host is an ordinary host array.  Synchronous.  Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, HIP. */
+int table_reorder(const float* src_pinned, float* dst_pinned, const int32_t* inv_rank_host, int64_t num_rows,
+                  int32_t dim, void* hip_stream);
+
 /* ---- per-kernel timing with HIP events on the handle's own streams (for the benchmark) ---- */
 int cache_profile_enable(fc_cache* c, int32_t on);   /* on=1 starts recording, 0 stops; resets totals when turned on */
 int cache_profile_count(void);                        /* number of timed kernels / copies                               */

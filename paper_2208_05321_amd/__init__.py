@@ -6,6 +6,8 @@ streams.  There is no CPU fallback: without the built library or without a GPU t
 """
 from .binding import (  # noqa: F401
     FreqCache,
+    FreqCounter,
+    table_reorder,
     FreqCacheError,
     load_library,
     FC_WARM,

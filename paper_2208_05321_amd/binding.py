@@ -26,7 +26,7 @@ EXPORTS = (
     "cache_create", "cache_warm", "cache_prepare", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
     "cache_check", "cache_destroy", "cache_last_stats", "cache_copy_state", "cache_last_lists", "cache_copy_rows",
     "cache_host_weight", "cache_strerror", "cache_profile_enable", "cache_profile_count", "cache_profile_name",
-    "cache_profile_get",
+    "cache_profile_get", "freq_create", "freq_add", "freq_build", "freq_destroy", "table_reorder",
 )
 
 
@@ -72,6 +72,11 @@ def load_library(path: str | None = None):
     L.cache_profile_name.argtypes = [i32]
     L.cache_profile_name.restype = ctypes.c_char_p
     L.cache_profile_get.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.freq_create.argtypes = [i64, vp, ctypes.POINTER(vp)]
+    L.freq_add.argtypes = [vp, vp, i64]
+    L.freq_build.argtypes = [vp, vp, vp, vp]
+    L.freq_destroy.argtypes = [vp]
+    L.table_reorder.argtypes = [vp, vp, vp, i64, i32, vp]
     for name in EXPORTS:
         if name not in ("cache_host_weight", "cache_strerror", "cache_profile_name"):
             getattr(L, name).restype = ctypes.c_int
@@ -213,3 +218,59 @@ class FreqCache:
             if cnt.value:
                 rep[self._L.cache_profile_name(k).decode()] = {"ms": ms.value, "launches": cnt.value}
         return rep
+
+
+class FreqCounter:
+    """Static module on the GPU: accumulate id counts over a trace, then build freq_rank (one C-ABI call each)."""
+
+    def __init__(self, num_rows: int, stream=None):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise FreqCacheError(-8, "no GPU visible; this library has no CPU path")
+        self._L = load_library()
+        self.num_rows = int(num_rows)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = ctypes.c_void_p()
+        rc = self._L.freq_create(self.num_rows, ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
+        self._h = h if rc == 0 else None
+        if rc:
+            raise FreqCacheError(rc, "freq_create")
+
+    def add(self, ids):
+        rc = self._L.freq_add(self._h, _ptr(ids), ids.numel())
+        if rc:
+            raise FreqCacheError(rc, "freq_add")
+
+    def build(self, with_counts: bool = False):
+        fr = np.empty(self.num_rows, dtype=np.int32)
+        inv = np.empty(self.num_rows, dtype=np.int32)
+        cnt = np.empty(self.num_rows, dtype=np.int32) if with_counts else None
+        rc = self._L.freq_build(self._h, fr.ctypes.data, inv.ctypes.data, _ptr(cnt))
+        if rc:
+            raise FreqCacheError(rc, "freq_build")
+        return (fr, inv, cnt) if with_counts else (fr, inv)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.freq_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def table_reorder(src_pinned, dst_pinned, inv_rank: np.ndarray, stream=None):
+    """dst[r] = src[inv_rank[r]] for two pinned torch tensors [N, D] (C-ABI call table_reorder)."""
+    import torch
+
+    L = load_library()
+    st = stream if stream is not None else torch.cuda.current_stream()
+    inv = np.ascontiguousarray(inv_rank, dtype=np.int32)
+    n, d = src_pinned.shape
+    rc = L.table_reorder(_ptr(src_pinned), _ptr(dst_pinned), inv.ctypes.data, n, d, ctypes.c_void_p(st.cuda_stream))
+    if rc:
+        raise FreqCacheError(rc, "table_reorder")

@@ -16,7 +16,7 @@ static const char* const kProfNames[P_COUNT] = {
     "h2d_block", "d2h_block", "flush_rows"};
 
 ProfScope::ProfScope(fc_cache* c_, int item_, hipStream_t s_) : c(c_), s(s_), item(item_) {
-    if (!c->prof_on) return;
+    if (!c || !c->prof_on) return;
     for (hipEvent_t* e : {&a, &b}) {
         if (!c->ev_pool.empty()) { *e = c->ev_pool.back(); c->ev_pool.pop_back(); }
         else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }

@@ -97,151 +97,6 @@ int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// backward, step 1: stable LSD radix sort of (slot, bag) by slot
-// ---------------------------------------------------------------------------------------------------------
-// First-pass key of lookup i: its slot, or the sentinel C if the slot is out of range.
-__device__ __forceinline__ int first_key(const int32_t* __restrict__ slots, int i, int C, bool& bad) {
-    const int k = slots[i];
-    if ((unsigned)k >= (unsigned)C) { bad = true; return C; }
-    return k;
-}
-
-// bag of lookup i: the largest b with offsets[b] <= i
-__device__ __forceinline__ int bag_of(const int64_t* __restrict__ offsets, int num_bags, int i) {
-    if (i < num_bags && offsets[i] == i && offsets[i + 1] == (int64_t)i + 1) return i;   // one id per bag
-    int lo = 0, hi = num_bags;
-    while (hi - lo > 1) {
-        const int mid = (int)(((int64_t)lo + hi) >> 1);
-        if (offsets[mid] <= i) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-__global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restrict__ keys_in, int n, int C, int shift,
-                                                          int radix_bits, int nblk, int32_t* __restrict__ ghist,
-                                                          Ctl* ctl, int first_pass) {
-    __shared__ int h[1 << RS_MAX_BITS];
-    const int radix = 1 << radix_bits, mask = radix - 1;
-    for (int d = threadIdx.x; d < radix; d += RS_THREADS) h[d] = 0;
-    __syncthreads();
-    const int tile0 = blockIdx.x * RS_TILE;
-    bool bad = false;
-#pragma unroll 4
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * RS_THREADS + threadIdx.x;
-        if (i < n) {
-            const int k = first_pass ? first_key(keys_in, i, C, bad) : keys_in[i];
-            atomicAdd(&h[(k >> shift) & mask], 1);
-        }
-    }
-    __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)d * nblk + blockIdx.x] = h[d];
-    if (bad) atomicOr(&ctl->async_flags, EF_BAD_SLOT);
-}
-
-// One wavefront per digit: exclusive scan of that digit's counts over the tiles; the digit total goes to dtot.
-__global__ __launch_bounds__(256) void k_sort_scan(int32_t* ghist, int nblk, int radix, int32_t* __restrict__ dtot) {
-    const int d = (blockIdx.x * 256 + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    if (d >= radix) return;
-    int carry = 0;
-    for (int b0 = 0; b0 < nblk; b0 += 64) {
-        const int b = b0 + lane;
-        const int v = b < nblk ? ghist[(size_t)d * nblk + b] : 0;
-        int x = v;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            int y = __shfl_up(x, o);
-            if (lane >= o) x += y;
-        }
-        if (b < nblk) ghist[(size_t)d * nblk + b] = carry + x - v;
-        carry += __shfl(x, 63);
-    }
-    if (lane == 0) dtot[d] = carry;
-}
-
-__global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __restrict__ keys_in,
-                                                             const int32_t* __restrict__ vals_in,
-                                                             const int64_t* __restrict__ offsets, int num_bags, int n,
-                                                             int C, int shift, int radix_bits, int nblk,
-                                                             const int32_t* __restrict__ ghist,
-                                                             const int32_t* __restrict__ dtot,
-                                                             int32_t* __restrict__ keys_out,
-                                                             int32_t* __restrict__ vals_out, int first_pass) {
-    constexpr int NW = RS_THREADS / 64;
-    __shared__ int base[1 << RS_MAX_BITS];     // where this tile's run of each digit starts in the output
-    __shared__ int wc[NW][1 << RS_MAX_BITS];   // per-wavefront digit counts, then exclusive offsets
-    __shared__ int lds[NW];
-    const int radix = 1 << radix_bits, mask = radix - 1;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    {   // digit bases: exclusive scan of the digit totals, plus this tile's offset within the digit
-        const int per = (radix + RS_THREADS - 1) / RS_THREADS;
-        const int d0 = tid * per;
-        int local = 0;
-        for (int k = 0; k < per; ++k) if (d0 + k < radix) local += dtot[d0 + k];
-        int tot;
-        int run = block_excl_scan<RS_THREADS>(local, tot, lds);
-        for (int k = 0; k < per; ++k) {
-            const int d = d0 + k;
-            if (d < radix) {
-                base[d] = run + ghist[(size_t)d * nblk + blockIdx.x];
-                run += dtot[d];
-            }
-        }
-        for (int d = tid; d < radix; d += RS_THREADS) {
-#pragma unroll
-            for (int k = 0; k < NW; ++k) wc[k][d] = 0;
-        }
-    }
-    __syncthreads();
-    const int tile0 = blockIdx.x * RS_TILE + w * (RS_TILE / NW);
-    const uint64_t lt = (1ull << lane) - 1ull;
-    int key[RS_ITEMS], val[RS_ITEMS], lrank[RS_ITEMS];
-    bool bad = false;
-#pragma unroll
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * 64 + lane;
-        const bool valid = i < n;
-        int k = 0, v = 0;
-        if (valid) {
-            if (first_pass) { k = first_key(keys_in, i, C, bad); v = bag_of(offsets, num_bags, i); }
-            else { k = keys_in[i]; v = vals_in[i]; }
-        }
-        const int d = (k >> shift) & mask;
-        uint64_t peers = __ballot(valid);
-        for (int b = 0; b < radix_bits; ++b) {
-            const bool one = (d >> b) & 1;
-            const uint64_t bm = __ballot(one);
-            peers &= one ? bm : ~bm;
-        }
-        const int before = __popcll(peers & lt);
-        int old = 0;
-        if (valid) old = wc[w][d];
-        if (valid && before == 0) wc[w][d] = old + __popcll(peers);
-        lrank[it] = old + before;
-        key[it] = k;
-        val[it] = v;
-    }
-    __syncthreads();
-    for (int d = tid; d < radix; d += RS_THREADS) {
-        int run = 0;
-#pragma unroll
-        for (int k = 0; k < NW; ++k) { const int cnt = wc[k][d]; wc[k][d] = run; run += cnt; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * 64 + lane;
-        if (i < n) {
-            const int d = (key[it] >> shift) & mask;
-            const int dest = base[d] + wc[w][d] + lrank[it];
-            keys_out[dest] = key[it];
-            vals_out[dest] = val[it];
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------------------
 // backward, step 2: chunked segmented reduction + SGD
 // ---------------------------------------------------------------------------------------------------------
 // A row-group owns BWD_CHUNK consecutive sorted lookups; a workgroup owns gpb such chunks in a row.
@@ -425,33 +280,12 @@ static int sort_pairs(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t
                       int64_t num_bags, const int32_t** kres, const int32_t** vres) {
     int bits = 1;
     while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
-    const int passes = (bits + RS_MAX_BITS - 1) / RS_MAX_BITS;
-    const int rb = (bits + passes - 1) / passes;
-    const int radix = 1 << rb;
-    const int64_t nblk = cdiv(n, RS_TILE);
-    const int32_t* kin = slots; const int32_t* vin = nullptr;
-    int32_t* kout = c->keysA; int32_t* vout = c->valsA;
-    for (int p = 0; p < passes; ++p) {
-        const int shift = p * rb;
-        {
-            ProfScope ps(c, P_SORT_HIST, st);
-            k_sort_hist<<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, (int)n, (int)c->C, shift, rb, (int)nblk, c->ghist, c->ctl, p == 0);
-        }
-        {
-            ProfScope ps(c, P_SORT_SCAN, st);
-            k_sort_scan<<<(unsigned)cdiv((int64_t)radix * 64, 256), 256, 0, st>>>(c->ghist, (int)nblk, radix, c->dtot);
-        }
-        {
-            ProfScope ps(c, P_SORT_SCATTER, st);
-            k_sort_scatter<<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, vin, offsets, (int)num_bags, (int)n, (int)c->C, shift, rb,
-                                                                 (int)nblk, c->ghist, c->dtot, kout, vout, p == 0);
-        }
-        kin = kout; vin = vout;
-        if (kout == c->keysA) { kout = c->keysB; vout = c->valsB; } else { kout = c->keysA; vout = c->valsA; }
-    }
-    FC_HIP(hipGetLastError());
-    *kres = kin; *vres = vin;
-    return FC_OK;
+    SortJob j;
+    j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
+    j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
+    j.keysA = c->keysA; j.valsA = c->valsA; j.keysB = c->keysB; j.valsB = c->valsB; j.ghist = c->ghist; j.dtot = c->dtot;
+    j.prof = c;
+    return radix_sort(j, st, kres, vres);
 }
 
 static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int64_t* rblocks, size_t* lds) {

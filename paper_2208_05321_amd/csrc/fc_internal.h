@@ -194,6 +194,24 @@ void pool_publish(fc_cache* c, int buf, int64_t rows);   // block `buf` holds `r
 void pool_wait(fc_cache* c, uint64_t seq);               // until block number `seq` (1-based) is in the host table
 uint64_t pool_published(fc_cache* c);
 
+// ---- radix sort (fc_sort.hip) ----
+enum SortSrc {
+    SORT_SRC_PAIRS = 0,   // keys_in / vals_in as given
+    SORT_SRC_SLOTS = 1,   // keys_in = slots of a batch (out-of-range -> sentinel `limit`, flag raised), value = bag of lookup i
+    SORT_SRC_COUNTS = 2   // keys_in = occurrence counts, key = limit - count (limit = largest count), value = i
+};
+struct SortJob {
+    int src = SORT_SRC_PAIRS;
+    const int32_t* keys_in = nullptr; const int32_t* vals_in = nullptr;
+    const int64_t* offsets = nullptr; int num_bags = 0;
+    int n = 0, limit = 0, bits = 1;
+    uint32_t* flags = nullptr;                 // device word for EF_BAD_SLOT, may be null
+    int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;   // n ints each
+    int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints, (1 << RS_MAX_BITS) ints
+    fc_cache* prof = nullptr;                  // where to book per-kernel times, may be null
+};
+int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres);
+
 // ---- device helpers ----
 template <int NT>
 __device__ __forceinline__ int block_excl_scan(int v, int& total, int* lds /* NT/64 ints */) {

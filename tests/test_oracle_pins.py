@@ -361,3 +361,41 @@ def test_error_paths_leave_state_unchanged():
     assert len(slots) == 0 and unchanged()
     out = o.embedding_bag_fwd(slots, np.zeros(4, dtype=np.int64))
     assert out.shape == (3, D) and (out == 0).all()
+
+
+# ---------------------------------------------------------------- static module (Section 4.2)
+def test_static_module_hand_example():
+    from oracle import count_ids, freq_rank_from_counts, reorder_table
+    # ids 0..5; occurrences: id3 x4, id1 x2, id5 x2, id0 x1, id2 x0, id4 x0
+    trace = [np.array([3, 1, 3, 5]), np.array([3, 0, 5, 1, 3])]
+    counts = count_ids(trace, 6)
+    assert counts.tolist() == [1, 2, 0, 4, 0, 2]
+    fr, inv = freq_rank_from_counts(counts)
+    assert inv.tolist() == [3, 1, 5, 0, 2, 4]          # high to low; equal counts: lower id first
+    assert fr.tolist() == [3, 1, 4, 0, 5, 2]
+    T = np.arange(12, dtype=np.float32).reshape(6, 2)
+    assert np.array_equal(reorder_table(T, inv), T[[3, 1, 5, 0, 2, 4]])
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_static_module_against_python_sort(seed):
+    from oracle import count_ids, freq_rank_from_counts
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(5, 400))
+    trace = [rng.zipf(1.3, size=300) % N for _ in range(3)]
+    counts = count_ids(trace, N)
+    brute = np.zeros(N, dtype=np.int64)
+    for t in trace:
+        for i in t:
+            brute[i] += 1
+    assert np.array_equal(counts, brute)
+    fr, inv = freq_rank_from_counts(counts)
+    expect = sorted(range(N), key=lambda i: (-int(counts[i]), i))
+    assert inv.tolist() == expect
+    assert np.array_equal(np.sort(fr), np.arange(N)) and np.array_equal(fr[inv], np.arange(N))
+    c = counts[inv]
+    assert (np.diff(c) <= 0).all()                               # high to low
+    same = np.diff(c) == 0
+    assert (np.diff(inv)[same] > 0).all()                        # ties by ascending id
+    with pytest.raises(ValueError):
+        count_ids([np.array([0, N])], N)

@@ -61,6 +61,8 @@ struct fc_cache {
     hipStream_t stream = nullptr, side = nullptr;
     hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
     bool evict_pending = false;
+    int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
+                                    // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through
     int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
     int evict_early = 2;            // when that kernel starts (tuning: FC_EVICT_EARLY): 0 after the miss fill, under
                                     // forward/backward; 1 right after the gather; 2 together with the miss fill

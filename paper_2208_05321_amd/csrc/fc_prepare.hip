@@ -546,7 +546,7 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
         }
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
         else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
-        else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, 1 << 20));
+        else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
     }
     if (M == 0 && n > 0) {
         {

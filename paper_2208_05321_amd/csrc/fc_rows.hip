@@ -113,7 +113,7 @@ int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows) {
     const int sh = shift_of(c->lpr);
     const int gpb = 256 >> sh;
     int64_t blocks = cdiv(rows, gpb);
-    if (blocks > (1 << 20)) blocks = 1 << 20;
+    if (blocks > c->fill_blocks) blocks = c->fill_blocks;
     ProfScope ps(c, P_MISS_FILL, s);
 #define FC_FILL(V) \
     k_fill_rows<V><<<(unsigned)blocks, 256, 0, s>>>(c->cache, c->fill_slots, (unsigned)c->C, c->host_dev, c->miss_ranks, (unsigned)c->N, \

@@ -37,7 +37,8 @@ struct Ctl {
 
 // Host-visible (pinned, mapped) copy of the decision, written by the planning kernel.
 struct HostCtl {
-    int32_t status, n_unique, n_miss, need, hit_ids, nfree, async_flags, pad;
+    int32_t status, n_unique, n_miss, need, hit_ids, nfree, async_flags;
+    int32_t ticket;      // written last: number of the cache_prepare call this record belongs to
 };
 
 enum ProfItem {
@@ -92,6 +93,7 @@ struct fc_cache {
     int64_t n_cap = 0;
     fc::Ctl* ctl = nullptr;
     fc::HostCtl* hctl = nullptr;    // pinned
+    int32_t ticket = 0;             // cache_prepare calls issued so far
     float* stage_dev = nullptr;     // [staging_rows][D] evicted-row block
     float* stage_dev2 = nullptr;    // staged mode: H2D block
     float* stage_pin = nullptr;     // staged mode: pinned block (both directions)

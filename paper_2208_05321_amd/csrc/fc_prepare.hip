@@ -116,7 +116,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restri
 __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
                                                     HostCtl* hctl, int32_t* __restrict__ moff,
                                                     int32_t* __restrict__ vtake, int32_t* __restrict__ voff,
-                                                    const int32_t* __restrict__ hitpart, int nmark) {
+                                                    const int32_t* __restrict__ hitpart, int nmark, int ticket) {
     __shared__ int lds[16];
     const int tid = threadIdx.x;
     int hits;
@@ -172,6 +172,8 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
         ctl->hit_ids = 0;
         hctl->status = status; hctl->n_unique = totU; hctl->n_miss = M; hctl->need = need;
         hctl->hit_ids = hits; hctl->nfree = nf; hctl->async_flags = (int32_t)ctl->async_flags;
+        __threadfence_system();                       // the record first, then the ticket the host is polling for
+        *reinterpret_cast<volatile int32_t*>(&hctl->ticket) = ticket;
     }
 }
 
@@ -443,6 +445,7 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     hipStream_t st = c->stream;
+    const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
     if (c->ps_valid) {                       // a sort nobody used: its scratch buffers must be free before the next one
         FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));
         c->ps_valid = false;
@@ -479,9 +482,8 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     }
     {
         ProfScope ps(c, P_RANK_PLAN, st);
-        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff, c->hitpart, (int)nmark);
+        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff, c->hitpart, (int)nmark, ticket);
     }
-    FC_HIP(hipEventRecord(c->ev_plan, st));
     // Last batch's evicted rows must have reached the host table before the victim lists and the block buffer
     // are reused and before any of those rows could be fetched again; the kernels above do not care.
     if (c->evict_pending) {
@@ -494,12 +496,24 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
                                                            c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C, transit_base, (int)c->staging_rows);
     }
     FC_HIP(hipGetLastError());
-    FC_HIP(hipEventSynchronize(c->ev_plan));
+    // The planning kernel writes its decision into pinned host memory and, last, this call's ticket: poll for it
+    // (cheaper than an event round trip, and the kernels enqueued behind it keep the GPU busy meanwhile).
     HostCtl h;
     {
         const volatile int32_t* hv = reinterpret_cast<const volatile int32_t*>(c->hctl);
+        uint64_t spins = 0;
+        while (hv[7] != ticket) {
+            __builtin_ia32_pause();
+            if ((++spins & 0x3FFF) == 0) {
+                const hipError_t q = hipStreamQuery(st);
+                if (q == hipSuccess) break;                          // stream drained: the record is there
+                if (q != hipErrorNotReady) { (void)hipGetLastError(); return FC_ERR_HIP; }
+            }
+        }
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        if (hv[7] != ticket) return FC_ERR_HIP;
         h.status = hv[0]; h.n_unique = hv[1]; h.n_miss = hv[2]; h.need = hv[3]; h.hit_ids = hv[4]; h.nfree = hv[5];
-        h.async_flags = hv[6]; h.pad = 0;
+        h.async_flags = hv[6]; h.ticket = hv[7];
     }
     if (h.status != FC_OK) return h.status;
     const int64_t M = h.n_miss, need = h.need;

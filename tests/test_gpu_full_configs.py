@@ -32,7 +32,7 @@ def log(msg):
     print(msg, flush=True)
 
 
-CASES = [("c3", 0.015, 4, True, 45), ("c4", 0.015, 3, False, 130), ("c5", 0.015, 3, False, 130)]
+CASES = [("c3", 0.015, 4, True, 45), ("c4", 0.015, 3, False, 130), ("c5", 0.015, 3, False, 130), ("avz", 0.015, 3, True, 15)]
 if EXTENDED:
     CASES += [("c3", 0.005, 4, False, 45), ("c3", 0.05, 3, False, 45), ("c4", 0.015, 3, True, 130), ("c5", 0.015, 3, True, 130)]
 

@@ -34,6 +34,7 @@ def test_config1_full(torch_cuda, warm):
 
 @pytest.mark.parametrize("name,scale,ratio,batches", [
     ("c2", 0.1, 0.015, 12), ("c3", 0.03, 0.03, 8), ("c4", 0.01, 0.03, 8), ("c5", 0.05, 0.015, 6),
+    ("avz", 0.1, 0.03, 6), ("c2d64", 0.1, 0.015, 5), ("c2d32", 0.1, 0.015, 5), ("c2d16", 0.1, 0.015, 5),
 ])
 def test_scaled_configs(torch_cuda, name, scale, ratio, batches):
     log(f"{name} at scale {scale}")

@@ -31,7 +31,7 @@ def test_cardinalities_sum_exactly():
 
 
 def test_workloads_are_deterministic_and_well_formed():
-    for name in ("c1", "c2", "c3", "c4", "c5", "c5u"):
+    for name in ("c1", "c2", "c3", "c4", "c5", "c5u", "avz", "c2d32"):
         a = make_workload(name, scale=0.002)
         b = make_workload(name, scale=0.002)
         assert np.array_equal(np.sort(a.freq_rank), np.arange(a.num_rows))       # a permutation

@@ -33,7 +33,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfc_fill.so")
 _lib = None
 
-CONFIG_NAMES = ("c1", "c2", "c3", "c4", "c5", "c5u")
+CONFIG_NAMES = ("c1", "c2", "c3", "c4", "c5", "c5u", "avz", "c2d64", "c2d32", "c2d16")
 
 
 def build_native(force: bool = False) -> str:
@@ -311,7 +311,8 @@ class Workload:
 
 def make_workload(name: str, scale: float = 1.0, cache_ratio: float = 0.015, num_batches: int | None = None,
                   seed: int = 0) -> Workload:
-    """The five benchmark configurations (plus "c5u", config 5's uniform-id run).
+    """The five benchmark configurations, plus "c5u" (config 5's uniform-id run), "avz" (the paper's second dataset
+    shape) and "c2d64/32/16" (config 2 at the per-rank row width of a 2/4/8-way column split).
 
     scale < 1 shrinks rows, cardinalities and batch together for CPU-sized tests; the
     cache stays at `cache_ratio` of the rows.
@@ -344,6 +345,17 @@ def make_workload(name: str, scale: float = 1.0, cache_ratio: float = 0.015, num
         N = per * F
         w = Workload(name, N, 256, int(N * cache_ratio), cards, 1.05, sc(8_192, 4), 200, 0.01,
                      multi_hot=True, id_dist="uniform" if name == "c5u" else "zipf", seed=seed)
+    elif name == "avz":
+        # second workload shape of the paper (Table 1, Section 5.2): 13 sparse features, 9,445,823 rows, batch 64K
+        N = sc(9_445_823, 1300)
+        cards = log_uniform_cardinalities(13, N, 10, sc(4_000_000, 10), seed + 3)
+        w = Workload(name, N, 128, int(N * cache_ratio), cards, 1.05, sc(65_536, 8), 200, 0.01, seed=seed)
+    elif name in ("c2d64", "c2d32", "c2d16"):
+        # config 2 as one rank of a column-wise (tensor-parallel) split over 2 / 4 / 8 GPUs sees it (Section 5.1):
+        # same ids and index work, dim / P columns per row
+        N = sc(10_000_000, 2600)
+        cards = log_uniform_cardinalities(26, N, 10, sc(2_000_000, 10), seed)
+        w = Workload(name, N, int(name[3:]), int(N * cache_ratio), cards, 1.05, sc(16_384, 8), 200, 0.01, seed=seed)
     else:
         raise ValueError(f"unknown config {name!r}")
     if num_batches is not None:

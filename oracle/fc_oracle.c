@@ -67,6 +67,9 @@ typedef struct fco {
     int32_t* evict_ranks;  /* [C] ascending cpu_row_idx                    */
     int32_t* evict_slots;  /* [C] slot of evict_ranks[j]                   */
     int32_t* fill_slots;   /* [C] fill_slots[j] receives miss_ranks[j]     */
+    /* look-ahead variant: rows of the previously prepared batch (ascending), also protected from eviction */
+    int32_t* prev_U;       /* [C]                                          */
+    int64_t n_prev;
 } fco;
 
 static int cmp_i32(const void* a, const void* b) {
@@ -90,7 +93,7 @@ static int contains_sorted(const int32_t* a, int64_t n, int32_t v) {
 void fco_destroy(fco* o) {
     if (!o) return;
     free(o->rank); free(o->cache); free(o->slot_rank); free(o->rank_slot);
-    free(o->miss_ranks); free(o->evict_ranks); free(o->evict_slots); free(o->fill_slots);
+    free(o->miss_ranks); free(o->evict_ranks); free(o->evict_slots); free(o->fill_slots); free(o->prev_U);
     free(o);
 }
 
@@ -117,7 +120,9 @@ int fco_create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float*
     o->evict_ranks = (int32_t*)malloc((size_t)C * 4);
     o->evict_slots = (int32_t*)malloc((size_t)C * 4);
     o->fill_slots = (int32_t*)malloc((size_t)C * 4);
-    if (!o->rank || !o->cache || !o->slot_rank || !o->rank_slot || !o->miss_ranks || !o->evict_ranks ||
+    o->prev_U = (int32_t*)malloc((size_t)C * 4);
+    o->n_prev = 0;
+    if (!o->prev_U ||  !o->rank || !o->cache || !o->slot_rank || !o->rank_slot || !o->miss_ranks || !o->evict_ranks ||
         !o->evict_slots || !o->fill_slots) { fco_destroy(o); return FCO_OOM; }
     memcpy(o->rank, freq_rank, (size_t)N * 4);
     for (int64_t r = 0; r < N; ++r) o->rank_slot[r] = -1;
@@ -134,8 +139,14 @@ int fco_create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float*
     return FCO_OK;
 }
 
-/* Algorithm 1: PrepareCache + PrepareCPURowIdxOnGPU. slots_out[n] receives gpu_row_idx per input id. */
-int fco_prepare(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out) {
+/* Algorithm 1: PrepareCache + PrepareCPURowIdxOnGPU. slots_out[n] receives gpu_row_idx per input id.
+ * protect_prev = 0: the algorithm as printed (the backlist is the current batch).
+ * protect_prev = 1: look-ahead variant (the paper's Future Work: "an input-id-prefetch method that looks ahead to
+ *   more input ids"): this batch is prepared while the previously prepared batch is still being trained on, so the
+ *   backlist is the union of both batches' rows.  If that leaves fewer evictable rows than needed the call fails
+ *   with BATCH_EXCEEDS_CACHE and changes nothing. */
+static int prepare_core(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out,
+                        int protect_prev) {
     if (!o || n < 0 || num_bags < 0 || (n > 0 && (!ids || !slots_out)) || !offsets) return FCO_INVALID_ARG;
     const int64_t N = o->N, C = o->C; const int32_t D = o->D;
     /* bag boundaries must tile [0, n) */
@@ -175,9 +186,12 @@ int fco_prepare(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, i
         int64_t nc = 0;
         for (int64_t s = 0; s < C; ++s) {
             int32_t k = o->slot_rank[s];
-            if (k >= 0 && !contains_sorted(U, nU, k)) { cand[nc].rank = k; cand[nc].slot = (int32_t)s; ++nc; }
+            if (k < 0 || contains_sorted(U, nU, k)) continue;
+            if (protect_prev && contains_sorted(o->prev_U, o->n_prev, k)) continue;
+            cand[nc].rank = k; cand[nc].slot = (int32_t)s; ++nc;
         }
-        if (nc < evict_num) { free(cand); free(r); free(U); return FCO_INVALID_ARG; } /* cannot happen when nU <= C */
+        /* without look-ahead this cannot happen when nU <= C */
+        if (nc < evict_num) { free(cand); free(r); free(U); return protect_prev ? FCO_BATCH_EXCEEDS_CACHE : FCO_INVALID_ARG; }
         qsort(cand, (size_t)nc, sizeof(cand_t), cmp_cand);
         nV = evict_num;
         /* report victims in ascending cpu_row_idx order */
@@ -212,8 +226,19 @@ int fco_prepare(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, i
     o->n_ids = n; o->n_unique = nU; o->n_hit_unique = nH; o->n_hit_ids = hit_ids;
     o->n_miss = nM; o->n_evict = nV;
     o->bytes_h2d = nM * (int64_t)D * 4; o->bytes_d2h = nV * (int64_t)D * 4;
+    memcpy(o->prev_U, U, (size_t)nU * 4);     /* this batch is the "previous" one of the next call */
+    o->n_prev = nU;
     free(r); free(U);
     return FCO_OK;
+}
+
+int fco_prepare(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out) {
+    return prepare_core(o, ids, n, offsets, num_bags, slots_out, 0);
+}
+
+int fco_prepare_lookahead(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags,
+                          int32_t* slots_out) {
+    return prepare_core(o, ids, n, offsets, num_bags, slots_out, 1);
 }
 
 /* EmbeddingBag, mode=sum, on the cached weight: out[b] = sum over the bag, in position order. */

@@ -41,6 +41,8 @@ def _load():
         L.fco_create.restype = ctypes.c_int
         L.fco_prepare.argtypes = [vp, vp, i64, vp, i64, vp]
         L.fco_prepare.restype = ctypes.c_int
+        L.fco_prepare_lookahead.argtypes = [vp, vp, i64, vp, i64, vp]
+        L.fco_prepare_lookahead.restype = ctypes.c_int
         L.fco_embedding_bag_fwd.argtypes = [vp, vp, i64, vp, i64, vp]
         L.fco_embedding_bag_fwd.restype = ctypes.c_int
         L.fco_embedding_bag_bwd_sgd.argtypes = [vp, vp, i64, vp, i64, vp, f32]
@@ -90,11 +92,13 @@ class Oracle:
 
     __del__ = close
 
-    def prepare(self, ids: np.ndarray, offsets: np.ndarray) -> np.ndarray:
+    def prepare(self, ids: np.ndarray, offsets: np.ndarray, lookahead: bool = False) -> np.ndarray:
+        """Algorithm 1; lookahead=True also protects the rows of the previously prepared batch."""
         ids = np.ascontiguousarray(ids, dtype=np.int64)
         offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         slots = np.empty(ids.shape[0], dtype=np.int32)
-        rc = self._L.fco_prepare(self._h, ids.ctypes.data, ids.shape[0], offsets.ctypes.data, offsets.shape[0] - 1,
+        fn = self._L.fco_prepare_lookahead if lookahead else self._L.fco_prepare
+        rc = fn(self._h, ids.ctypes.data, ids.shape[0], offsets.ctypes.data, offsets.shape[0] - 1,
                                  slots.ctypes.data)
         if rc:
             raise OracleError(rc)

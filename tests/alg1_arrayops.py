@@ -21,12 +21,14 @@ class ArrayOpsCache:
         self.missed = np.empty(0, dtype=np.int64)
         self.targets = np.empty(0, dtype=np.int64)
 
-    def prepare_cache(self, ids):
+    def prepare_cache(self, ids, also_protect=None):
+        """also_protect: extra cpu_row_idxs for the backlist (look-ahead: the previous batch's rows)."""
         rows_of_ids = self.idx_map[np.asarray(ids, dtype=np.int64)]
         cpu_row_idxs = np.unique(rows_of_ids)
         comm_cpu_row_idxs = cpu_row_idxs[np.isin(cpu_row_idxs, self.cache_idx_map, invert=True)]
         self.hit_ids = int(np.isin(rows_of_ids, self.cache_idx_map).sum())
-        self._prepare_cpu_row_idx_on_gpu(comm_cpu_row_idxs, cpu_row_idxs)
+        backlist = cpu_row_idxs if also_protect is None else np.union1d(cpu_row_idxs, also_protect)
+        self._prepare_cpu_row_idx_on_gpu(comm_cpu_row_idxs, backlist)
         # one gpu_row_idx per input id
         return np.array([np.nonzero(self.cache_idx_map == r)[0][0] for r in rows_of_ids], dtype=np.int64)
 

@@ -399,3 +399,76 @@ def test_static_module_against_python_sort(seed):
     assert (np.diff(inv)[same] > 0).all()                        # ties by ascending id
     with pytest.raises(ValueError):
         count_ids([np.array([0, N])], N)
+
+
+# ---------------------------------------------------------------- look-ahead variant (Future Work section)
+@pytest.mark.parametrize("seed", range(8))
+def test_lookahead_against_array_ops_algorithm1(seed):
+    """Backlist = rows of this batch and of the previously prepared one."""
+    rng = np.random.default_rng(500 + seed)
+    N = int(rng.integers(20, 80))
+    C = int(rng.integers(6, 14))
+    fr = rng.permutation(N).astype(np.int32)
+    host_a = rand_table(N, 2, seed)
+    host_b = host_a.copy()
+    o = Oracle(fr, host_a, C, warm=bool(seed % 2))
+    ref = ArrayOpsCache(fr, host_b, C, warm=bool(seed % 2))
+    prev = None
+    for t in range(40):
+        k = int(rng.integers(1, C // 2 + 1))          # two batches always fit together
+        ids = rng.permutation(N)[:k].astype(np.int64)
+        look = prev is not None and t % 3 != 0       # mix plain and look-ahead calls
+        slots_ref = ref.prepare_cache(ids, also_protect=prev if look else None)
+        slots = o.prepare(ids, one_hot_offsets(k), lookahead=look)
+        L = o.last_lists()
+        assert np.array_equal(slots, slots_ref) and np.array_equal(o.slot_rank, ref.cache_idx_map)
+        assert np.array_equal(L["evict_ranks"], ref.evicted) and np.array_equal(L["fill_slots"], ref.targets)
+        if look:
+            assert len(np.intersect1d(L["evict_ranks"], prev)) == 0      # previous batch's rows stay
+            assert (o.rank_slot[prev] >= 0).all()
+        prev = np.unique(fr[ids])
+        check_maps(o)
+
+
+def test_lookahead_schedule_is_transparent():
+    """The schedule the look-ahead is for: batch t+1 is prepared BEFORE batch t's forward/backward run.
+    Because batch t's rows are protected, the result still equals no-cache training."""
+    rng = np.random.default_rng(77)
+    N, D, C = 120, 4, 30
+    fr = rng.permutation(N).astype(np.int32)
+    inv = np.argsort(fr)
+    W = rand_table(N, D, 5)
+    host = W[inv].copy()
+    o = Oracle(fr, host, C, warm=True)
+    batches = []
+    for t in range(40):
+        n = int(rng.integers(1, 14))
+        ids = rng.permutation(N)[:n][rng.integers(0, n, size=n + 2)].astype(np.int64)
+        batches.append((ids, one_hot_offsets(len(ids)), rng.standard_normal((len(ids), D)).astype(np.float32)))
+    W_ref = W.copy()
+    outs_ref = no_cache_training(W_ref, batches, 0.1)
+    slots_cur = o.prepare(batches[0][0], batches[0][1])
+    for t, (ids, offsets, grad) in enumerate(batches):
+        slots_next = o.prepare(batches[t + 1][0], batches[t + 1][1], lookahead=True) if t + 1 < len(batches) else None
+        out = o.embedding_bag_fwd(slots_cur, offsets)
+        assert np.array_equal(out, outs_ref[t])
+        o.embedding_bag_bwd_sgd(slots_cur, offsets, grad, 0.1)
+        slots_cur = slots_next
+    o.flush()
+    assert np.array_equal(host, W_ref[inv])
+
+
+def test_lookahead_fails_cleanly_when_two_batches_do_not_fit():
+    rng = np.random.default_rng(9)
+    N, C = 60, 10
+    fr = rng.permutation(N).astype(np.int32)
+    o = Oracle(fr, rand_table(N, 2), C, warm=True)
+    a = np.argsort(fr)[20:28].astype(np.int64)        # 8 rows, none resident
+    b = np.argsort(fr)[30:38].astype(np.int64)        # 8 other rows: 16 > 10 together
+    o.prepare(a, one_hot_offsets(8))
+    sr, rs = o.slot_rank, o.rank_slot
+    with pytest.raises(OracleError) as e:
+        o.prepare(b, one_hot_offsets(8), lookahead=True)
+    assert e.value.name == "BATCH_EXCEEDS_CACHE"
+    assert np.array_equal(sr, o.slot_rank) and np.array_equal(rs, o.rank_slot)
+    o.prepare(b, one_hot_offsets(8))                  # the plain call fits

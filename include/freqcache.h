@@ -124,6 +124,22 @@ int cache_warm(fc_cache* c);
 int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                   int32_t* slots_dev);
 
+/* Look-ahead (the paper's Future Work: an input-id prefetch that looks ahead to more input ids): Algorithm 1 for the
+ * NEXT batch, issued while the batch of the latest cache_prepare / cache_prepare_next is still being trained on.
+ * Same arguments, results and errors as cache_prepare, with two differences:
+ *   - the rows of that previous batch are protected from eviction as well (the backlist of Algorithm 1 is the union
+ *     of both batches), so the forward / backward calls of the previous batch may be enqueued after this call; if too
+ *     few evictable rows remain the call fails with FC_ERR_BATCH_EXCEEDS_CACHE and changes nothing (the caller then
+ *     finishes the current batch and uses cache_prepare);
+ *   - the work is enqueued on a library-owned stream and overlaps the caller's stream; ids_dev / offsets_dev must be
+ *     complete on the caller's stream at the time of the call and stay untouched until cache_advance.
+ * Usage:  cache_prepare(batch 0);  loop { cache_prepare_next(batch t+1, slots_next); fwd(t); bwd(t); cache_advance(); } */
+int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                       int32_t* slots_dev);
+/* Makes the batch of the latest cache_prepare_next the current one: work enqueued on the caller's stream after this
+ * call sees its rows resident and its slots written.  Asynchronous (a stream-to-stream dependency). */
+int cache_advance(fc_cache* c);
+
 /* EmbeddingBag, mode "sum", on the cached weight (Section 4.3: the framework's embedding op runs on the
  * cached weight after the cache step):  out[b, :] = sum_{i in bag b} cached_weight[slots[i], :], summed
  * in position order; an empty bag gives zeros.

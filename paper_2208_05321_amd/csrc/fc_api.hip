@@ -32,6 +32,7 @@ void prof_collect(fc_cache* c) {
     (void)hipStreamSynchronize(c->stream);
     (void)hipStreamSynchronize(c->side);
     if (c->aux) (void)hipStreamSynchronize(c->aux);
+    if (c->pre) (void)hipStreamSynchronize(c->pre);
     for (const ProfSpan& sp : c->spans) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) { c->prof_ms[sp.item] += ms; c->prof_n[sp.item] += 1; }
@@ -67,11 +68,15 @@ __global__ void k_set_ctl(Ctl* ctl, int nfree) {
 
 static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
+    for (hipStream_t x : {c->pre, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
+    c->next_pending = false; c->last_pst = c->stream;
+    for (PresortRec& r : c->rec) r.valid = false;
     if (c->dma_evict) { pool_wait(c, pool_published(c)); c->blk_rows[0] = c->blk_rows[1] = 0; }
     const int64_t words = c->NB * RT_WORDS;
     k_iota_or_neg<<<1024, 256, 0, st>>>(c->rank_slot, c->N, warm ? c->C : 0);
     k_iota_or_neg<<<256, 256, 0, st>>>(c->slot_rank, c->C, warm ? c->C : 0);
     k_bits_prefix<<<256, 256, 0, st>>>(c->ubits, words, 0);
+    k_bits_prefix<<<256, 256, 0, st>>>(c->pbits, words, 0);
     k_bits_prefix<<<256, 256, 0, st>>>(c->rbits, words, warm ? c->C : 0);
     k_set_ctl<<<1, 1, 0, st>>>(c->ctl, warm ? 0 : (int)c->C);
     FC_HIP(hipGetLastError());
@@ -99,16 +104,20 @@ static void destroy(fc_cache* c) {
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
                     (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
                     (void*)c->miss_ranks, (void*)c->vrank, (void*)c->vslot, (void*)c->fill_slots, (void*)c->rbuf,
-                    (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->keysA, (void*)c->valsA,
-                    (void*)c->keysB, (void*)c->valsB, (void*)c->ghist, (void*)c->dtot, (void*)c->part, (void*)c->pmeta})
+                    (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->part, (void*)c->pmeta, (void*)c->pbits})
         if (p) (void)hipFree(p);
+    for (SortBufs& sb : c->sb)
+        for (void* p : {(void*)sb.keysA, (void*)sb.valsA, (void*)sb.keysB, (void*)sb.valsB, (void*)sb.ghist, (void*)sb.dtot})
+            if (p) (void)hipFree(p);
+    for (PresortRec& r : c->rec) if (r.ev_sorted) (void)hipEventDestroy(r.ev_sorted);
     for (void* p : {(void*)c->hctl, (void*)c->stage_pin, (void*)c->list_pin}) if (p) (void)hipHostFree(p);
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_sorted}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_s_now, c->ev_pre_done}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->aux) (void)hipStreamDestroy(c->aux);
+    if (c->pre) (void)hipStreamDestroy(c->pre);
     delete c;
 }
 
@@ -152,6 +161,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipMalloc((void**)&c->cache, (size_t)C * D * 4));
     FC_HIP(hipMalloc((void**)&c->ubits, words * 4));
     FC_HIP(hipMalloc((void**)&c->rbits, words * 4));
+    FC_HIP(hipMalloc((void**)&c->pbits, words * 4));
     FC_HIP(hipMalloc((void**)&c->tcount, (size_t)cdiv(C, 1024) * 4));
     FC_HIP(hipMalloc((void**)&c->hitpart, 256 * 4));
     FC_HIP(hipMalloc((void**)&c->bsum, (size_t)c->NB * 3 * 4));
@@ -189,8 +199,11 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     }
     FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
     FC_HIP(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
+    FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
+    c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_sorted})
+    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done,
+                          &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
     if (c->dma_evict) {
@@ -204,6 +217,16 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
 }  // namespace fc
 
 using namespace fc;
+
+// the caller's stream takes over from the look-ahead stream: everything cache_prepare_next enqueued comes first
+static int adopt_next(fc_cache* c) {
+    if (c->next_pending || c->last_pst != c->stream) {
+        FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));
+        c->next_pending = false;
+        c->last_pst = c->stream;
+    }
+    return FC_OK;
+}
 
 extern "C" {
 
@@ -239,6 +262,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
 int cache_warm(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_TRY(adopt_next(c));
     FC_HIP(hipStreamSynchronize(c->stream));
     FC_HIP(hipStreamSynchronize(c->side));
     c->evict_pending = false;
@@ -247,7 +271,43 @@ int cache_warm(fc_cache* c) {
 
 int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                   int32_t* slots_dev) {
-    return prepare_impl(c, ids_dev, n, offsets_dev, num_bags, slots_dev);
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_TRY(adopt_next(c));
+    return prepare_impl(c, c->stream, false, ids_dev, n, offsets_dev, num_bags, slots_dev);
+}
+
+int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                       int32_t* slots_dev) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    // everything the caller has enqueued so far (the backward pass of the batch before the current one, and the
+    // input buffers of this call) is complete before this call's row movement, or before all of it when the last
+    // prepare ran on the caller's stream
+    FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
+    if (c->last_pst != c->pre) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
+    const int rc = prepare_impl(c, c->pre, true, ids_dev, n, offsets_dev, num_bags, slots_dev);
+    c->pst = c->stream;
+    if (rc != FC_OK) {
+        // nothing changed; keep the streams ordered all the same
+        FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
+        c->last_pst = c->pre; c->next_pending = true;
+        return rc;
+    }
+    FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
+    c->last_pst = c->pre;
+    c->next_pending = true;
+    return FC_OK;
+}
+
+int cache_advance(fc_cache* c) {
+    if (!c) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    if (c->next_pending) {
+        FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));
+        c->next_pending = false;
+    }
+    return FC_OK;
 }
 
 int embedding_bag_fwd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
@@ -263,9 +323,10 @@ int embedding_bag_bwd_sgd(fc_cache* c, const int32_t* slots_dev, int64_t n, cons
 int cache_flush(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_TRY(adopt_next(c));
     FC_HIP(hipStreamSynchronize(c->side));      // pending evicted rows first: flush must not be overtaken
     c->evict_pending = false;
-    FC_TRY(dma_quiesce(c));
+    FC_TRY(dma_quiesce(c, c->stream));
     if (c->flags & FC_TRANSMIT_STAGED) {
         // the cached weight is contiguous: bulk-copy slot ranges, scatter the resident ones on the host
         std::vector<int32_t> sr((size_t)c->C);
@@ -293,10 +354,11 @@ int cache_flush(fc_cache* c) {
 int cache_check(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_TRY(adopt_next(c));
     FC_HIP(hipStreamSynchronize(c->aux));
     FC_HIP(hipStreamSynchronize(c->stream));
     FC_HIP(hipStreamSynchronize(c->side));
-    FC_TRY(dma_quiesce(c));
+    FC_TRY(dma_quiesce(c, c->stream));
     FC_HIP(hipStreamSynchronize(c->stream));
     Ctl h;
     FC_HIP(hipMemcpy(&h, c->ctl, sizeof(Ctl), hipMemcpyDeviceToHost));
@@ -322,6 +384,7 @@ int cache_last_stats(const fc_cache* c, fc_stats* out) {
 int cache_copy_state(fc_cache* c, int32_t* slot_rank_host, int32_t* rank_slot_host) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->pre));
     FC_HIP(hipStreamSynchronize(c->stream));
     if (slot_rank_host) FC_HIP(hipMemcpy(slot_rank_host, c->slot_rank, (size_t)c->C * 4, hipMemcpyDeviceToHost));
     if (rank_slot_host) {
@@ -337,6 +400,7 @@ int cache_last_lists(fc_cache* c, int32_t* miss_ranks_host, int32_t* evict_ranks
     if (!c) return FC_ERR_INVALID_ARG;
     if (!c->have_lists) return FC_OK;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->pre));
     FC_HIP(hipStreamSynchronize(c->stream));
     const size_t m = (size_t)c->last.n_miss * 4, v = (size_t)c->last.n_evict * 4;
     if (miss_ranks_host && m) FC_HIP(hipMemcpy(miss_ranks_host, c->miss_ranks, m, hipMemcpyDeviceToHost));
@@ -349,6 +413,7 @@ int cache_last_lists(fc_cache* c, int32_t* miss_ranks_host, int32_t* evict_ranks
 int cache_copy_rows(fc_cache* c, float* rows_host) {
     if (!c || !rows_host) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipStreamSynchronize(c->pre));
     FC_HIP(hipStreamSynchronize(c->stream));
     FC_HIP(hipMemcpy(rows_host, c->cache, (size_t)c->C * c->D * 4, hipMemcpyDeviceToHost));
     return FC_OK;

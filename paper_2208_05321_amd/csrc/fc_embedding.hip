@@ -244,26 +244,32 @@ __global__ __launch_bounds__(256) void k_bwd_fixup(int C, float* cache, int D, i
 // threads per workgroup of the reduction: at most 64 chunks per workgroup
 static inline int bwd_threads(int lpr) { int t = 32 * lpr; if (t > 256) t = 256; if (t < 64) t = 64; return t; }
 
-static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
-    if (n > c->sort_cap) {
-        FC_HIP(hipStreamSynchronize(c->stream));
-        for (int32_t** p : {&c->keysA, &c->valsA, &c->keysB, &c->valsB}) { if (*p) FC_HIP(hipFree(*p)); *p = nullptr; }
-        c->sort_cap = 0;
+// (Re)allocation of sort scratch and of the reduction's partial rows; growth is rare and waits for the whole device.
+static int ensure_sort(SortBufs& sb, int64_t n) {
+    const int64_t nblk = cdiv(n, RS_TILE);
+    if (n > sb.cap) {
+        FC_HIP(hipDeviceSynchronize());
+        for (int32_t** p : {&sb.keysA, &sb.valsA, &sb.keysB, &sb.valsB}) { if (*p) FC_HIP(hipFree(*p)); *p = nullptr; }
+        sb.cap = 0;
         const int64_t cap = n + n / 4 + 1024;
-        for (int32_t** p : {&c->keysA, &c->valsA, &c->keysB, &c->valsB}) FC_HIP(hipMalloc((void**)p, (size_t)cap * 4));
-        c->sort_cap = cap;
+        for (int32_t** p : {&sb.keysA, &sb.valsA, &sb.keysB, &sb.valsB}) FC_HIP(hipMalloc((void**)p, (size_t)cap * 4));
+        sb.cap = cap;
     }
     const int64_t gh = nblk << RS_MAX_BITS;
-    if (gh > c->ghist_cap) {
-        FC_HIP(hipStreamSynchronize(c->stream));
-        if (c->ghist) FC_HIP(hipFree(c->ghist));
-        c->ghist = nullptr; c->ghist_cap = 0;
-        FC_HIP(hipMalloc((void**)&c->ghist, (size_t)(gh + gh / 4) * 4));
-        c->ghist_cap = gh + gh / 4;
+    if (gh > sb.ghist_cap) {
+        FC_HIP(hipDeviceSynchronize());
+        if (sb.ghist) FC_HIP(hipFree(sb.ghist));
+        sb.ghist = nullptr; sb.ghist_cap = 0;
+        FC_HIP(hipMalloc((void**)&sb.ghist, (size_t)(gh + gh / 4) * 4));
+        sb.ghist_cap = gh + gh / 4;
     }
-    if (!c->dtot) FC_HIP(hipMalloc((void**)&c->dtot, (size_t)(1 << RS_MAX_BITS) * 4));
+    if (!sb.dtot) FC_HIP(hipMalloc((void**)&sb.dtot, (size_t)(1 << RS_MAX_BITS) * 4));
+    return FC_OK;
+}
+
+static int ensure_part(fc_cache* c, int64_t groups) {
     if (groups > c->part_groups) {
-        FC_HIP(hipStreamSynchronize(c->stream));
+        FC_HIP(hipDeviceSynchronize());
         if (c->part) FC_HIP(hipFree(c->part));
         if (c->pmeta) FC_HIP(hipFree(c->pmeta));
         c->part = nullptr; c->pmeta = nullptr; c->part_groups = 0;
@@ -276,14 +282,14 @@ static int ensure_bwd(fc_cache* c, int64_t n, int64_t nblk, int64_t groups) {
 }
 
 // Stable sort of the batch's (slot, bag) pairs by slot on stream `st`; *kres / *vres receive the sorted arrays.
-static int sort_pairs(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t n, const int64_t* offsets,
+static int sort_pairs(fc_cache* c, SortBufs& sb, hipStream_t st, const int32_t* slots, int64_t n, const int64_t* offsets,
                       int64_t num_bags, const int32_t** kres, const int32_t** vres) {
     int bits = 1;
     while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
     SortJob j;
     j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
     j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
-    j.keysA = c->keysA; j.valsA = c->valsA; j.keysB = c->keysB; j.valsB = c->valsB; j.ghist = c->ghist; j.dtot = c->dtot;
+    j.keysA = sb.keysA; j.valsA = sb.valsA; j.keysB = sb.keysB; j.valsB = sb.valsB; j.ghist = sb.ghist; j.dtot = sb.dtot;
     j.prof = c;
     return radix_sort(j, st, kres, vres);
 }
@@ -295,20 +301,24 @@ static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int
     *lds = (size_t)rgpb * BWD_CHUNK * 8 + (size_t)rgpb * sizeof(BwdMeta) + (size_t)rgpb * 2 * c->D * 4;
 }
 
-// Called by cache_prepare once the slots of the batch are on their way: the sort needs nothing but the slots and
-// the bag offsets, so it runs on the auxiliary stream while the missing rows are still crossing the host link.
+// Called by cache_prepare / cache_prepare_next once the slots of the batch are on their way: the sort needs nothing
+// but the slots and the bag offsets, so it runs on the auxiliary stream while the missing rows are still crossing
+// the host link.  Two records alternate, so that the sort of the next batch does not disturb the current one's.
 int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags) {
-    c->ps_valid = false;
+    const int k = c->rec_next;
+    c->rec_next ^= 1;
+    PresortRec& r = c->rec[k];
+    r.valid = false;
     if (!c->presort || n <= 0 || num_bags <= 0) return FC_OK;
-    int rthreads; int64_t rblocks; size_t lds;
-    bwd_geometry(c, n, &rthreads, &rblocks, &lds);
-    FC_TRY(ensure_bwd(c, n, cdiv(n, RS_TILE), rblocks));
-    FC_HIP(hipEventRecord(c->ev_slots, c->stream));
+    FC_TRY(ensure_sort(c->sb[k], n));
+    FC_HIP(hipEventRecord(c->ev_slots, c->pst));
     FC_HIP(hipStreamWaitEvent(c->aux, c->ev_slots, 0));
-    FC_TRY(sort_pairs(c, c->aux, slots, n, offsets, num_bags, &c->ps_keys, &c->ps_vals));
-    FC_HIP(hipEventRecord(c->ev_sorted, c->aux));
-    c->ps_slots = slots; c->ps_n = n; c->ps_offsets = offsets; c->ps_bags = num_bags;
-    c->ps_valid = true;
+    // the record's previous sort was read by a backward pass on the caller's stream, enqueued before this call
+    if (c->pst != c->stream) FC_HIP(hipStreamWaitEvent(c->aux, c->ev_s_now, 0));
+    FC_TRY(sort_pairs(c, c->sb[k], c->aux, slots, n, offsets, num_bags, &r.keys, &r.vals));
+    FC_HIP(hipEventRecord(r.ev_sorted, c->aux));
+    r.slots = slots; r.n = n; r.offsets = offsets; r.bags = num_bags;
+    r.valid = true;
     return FC_OK;
 }
 
@@ -322,16 +332,20 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     hipStream_t st = c->stream;
     int rthreads; int64_t rblocks; size_t lds;
     bwd_geometry(c, n, &rthreads, &rblocks, &lds);
-    const int32_t* kin; const int32_t* vin;
-    if (c->ps_valid && c->ps_slots == slots && c->ps_n == n && c->ps_offsets == offsets && c->ps_bags == num_bags) {
-        FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));      // sorted ahead of time by cache_prepare
-        kin = c->ps_keys; vin = c->ps_vals;
-    } else {
-        if (c->ps_valid) FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));   // the scratch buffers are shared
-        FC_TRY(ensure_bwd(c, n, cdiv(n, RS_TILE), rblocks));
-        FC_TRY(sort_pairs(c, st, slots, n, offsets, num_bags, &kin, &vin));
+    FC_TRY(ensure_part(c, rblocks));
+    const int32_t* kin = nullptr; const int32_t* vin = nullptr;
+    for (PresortRec& r : c->rec) {
+        if (r.valid && r.slots == slots && r.n == n && r.offsets == offsets && r.bags == num_bags) {
+            FC_HIP(hipStreamWaitEvent(st, r.ev_sorted, 0));      // sorted ahead of time
+            kin = r.keys; vin = r.vals;
+            r.valid = false;
+            break;
+        }
     }
-    c->ps_valid = false;
+    if (!kin) {
+        FC_TRY(ensure_sort(c->sb[2], n));
+        FC_TRY(sort_pairs(c, c->sb[2], st, slots, n, offsets, num_bags, &kin, &vin));
+    }
     const int sh = shift_of(c->lpr);
     {
         ProfScope ps(c, P_BWD_REDUCE, st);

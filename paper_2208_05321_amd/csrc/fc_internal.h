@@ -51,6 +51,19 @@ struct ProfSpan { int item; hipEvent_t a, b; };
 
 struct ScatterPool;   // host threads that scatter evicted-row blocks into the host table (fc_worker.hip)
 
+// Scratch of one radix sort of a batch's (slot, bag) pairs, and the record of a sort started ahead of time.
+struct SortBufs {
+    int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr, *ghist = nullptr, *dtot = nullptr;
+    int64_t cap = 0, ghist_cap = 0;
+};
+struct PresortRec {
+    bool valid = false;
+    const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
+    int64_t n = 0, bags = 0;
+    const int32_t *keys = nullptr, *vals = nullptr;
+    hipEvent_t ev_sorted = nullptr;
+};
+
 }  // namespace fc
 
 struct fc_cache {
@@ -60,6 +73,12 @@ struct fc_cache {
     int32_t flags = 0;
     int device = 0;
     hipStream_t stream = nullptr, side = nullptr;
+    // Look-ahead (cache_prepare_next): the next batch is prepared on `pre` while the caller's stream still trains on
+    // the current one.  pst = the stream the cache_prepare / cache_prepare_next in progress enqueues on.
+    hipStream_t pre = nullptr, pst = nullptr, last_pst = nullptr;
+    hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr;
+    bool next_pending = false;
+    uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
     bool evict_pending = false;
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
@@ -118,9 +137,7 @@ struct fc_cache {
     bool own_host = false;
 
     // backward-pass scratch
-    int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;
-    int32_t *ghist = nullptr, *dtot = nullptr;
-    int64_t sort_cap = 0, ghist_cap = 0;
+    fc::SortBufs sb[3];             // [0], [1]: sorts started by cache_prepare (alternating); [2]: sorts inside the backward call
     float* part = nullptr;          // [groups][2][D] partial sums of slots spanning chunk borders
     int32_t* pmeta = nullptr;       // [groups][4]
     int64_t part_groups = 0;
@@ -128,11 +145,9 @@ struct fc_cache {
     // sort of the (slot, bag) pairs started by cache_prepare on the auxiliary stream
     bool presort = true;            // FC_NO_PRESORT clears it
     hipStream_t aux = nullptr;
-    hipEvent_t ev_slots = nullptr, ev_sorted = nullptr;
-    bool ps_valid = false;
-    const int32_t* ps_slots = nullptr; const int64_t* ps_offsets = nullptr;
-    int64_t ps_n = 0, ps_bags = 0;
-    const int32_t *ps_keys = nullptr, *ps_vals = nullptr;
+    hipEvent_t ev_slots = nullptr;
+    fc::PresortRec rec[2];
+    int rec_next = 0;
 
     // last prepare
     fc_stats last = {};
@@ -175,9 +190,10 @@ void prof_collect(fc_cache* c);
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // entry points implemented across the sources
-int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots);
+int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
+                 int64_t num_bags, int32_t* slots);
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
-int dma_quiesce(fc_cache* c);
+int dma_quiesce(fc_cache* c, hipStream_t st);
 int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags);
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
              const float* grad, float lr);

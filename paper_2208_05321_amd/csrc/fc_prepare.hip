@@ -90,12 +90,19 @@ __global__ __launch_bounds__(MARK_THREADS) void k_remap_mark(const int64_t* __re
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restrict__ ubits4,
                                                            const uint4* __restrict__ rbits4,
+                                                           const uint4* __restrict__ pbits4, int protect_prev,
                                                            int32_t* __restrict__ bsum, int NB) {
     __shared__ int lds[3][RT_THREADS / 64];
     const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
-    const uint4 u = ubits4[idx], r = rbits4[idx];
+    const uint4 u = ubits4[idx];
+    uint4 r = rbits4[idx];
+    const int cm0 = __popc(u.x & ~r.x) + __popc(u.y & ~r.y) + __popc(u.z & ~r.z) + __popc(u.w & ~r.w);
+    if (protect_prev) {        // look-ahead: rows of the previously prepared batch are not evictable either
+        const uint4 p = pbits4[idx];
+        r.x &= ~p.x; r.y &= ~p.y; r.z &= ~p.z; r.w &= ~p.w;
+    }
     int cu = __popc(u.x) + __popc(u.y) + __popc(u.z) + __popc(u.w);
-    int cm = __popc(u.x & ~r.x) + __popc(u.y & ~r.y) + __popc(u.z & ~r.z) + __popc(u.w & ~r.w);
+    int cm = cm0;
     int cc = __popc(r.x & ~u.x) + __popc(r.y & ~u.y) + __popc(r.z & ~u.z) + __popc(r.w & ~u.w);
     cu = wave_sum(cu); cm = wave_sum(cm); cc = wave_sum(cc);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -141,7 +148,18 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
     else if (totU > C) status = FC_ERR_BATCH_EXCEEDS_CACHE;
     const int M = carryM;
     int need = M - nfree;
-    if (need < 0 || status != FC_OK) need = 0;
+    if (need < 0) need = 0;
+    {   // enough evictable rows?  (always, unless the look-ahead protects the previous batch as well)
+        int totC = 0;
+        for (int base = 0; base < NB; base += 1024) {
+            const int b = base + tid;
+            int t;
+            (void)block_excl_scan<1024>(b < NB ? bsum[(size_t)2 * NB + b] : 0, t, lds);
+            totC += t;
+        }
+        if (status == FC_OK && need > totC) status = FC_ERR_BATCH_EXCEEDS_CACHE;
+    }
+    if (status != FC_OK) need = 0;
     // Victims: walk tiles from the highest ranks down; `above` = evictable rows in tiles of larger rank.
     int carry = 0;
     for (int base = 0; base < NB; base += 1024) {
@@ -180,7 +198,8 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
 // ---------------------------------------------------------------------------------------------------------
 // K2c  per tile: write the missing ranks (ascending), pick and retire the victims, update rbits, clear ubits.
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* rbits4, const Ctl* __restrict__ ctl,
+__global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* rbits4, uint4* pbits4, int protect_prev,
+                                                          const Ctl* __restrict__ ctl,
                                                           const int32_t* __restrict__ moff,
                                                           const int32_t* __restrict__ vtake,
                                                           const int32_t* __restrict__ voff,
@@ -197,14 +216,16 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
         return;
     }
     const uint4 r4 = rbits4[idx];
+    const uint4 p4 = pbits4[idx];
     const uint32_t uw[4] = {u4.x, u4.y, u4.z, u4.w};
     const uint32_t rw[4] = {r4.x, r4.y, r4.z, r4.w};
+    const uint32_t pw[4] = {protect_prev ? p4.x : 0u, protect_prev ? p4.y : 0u, protect_prev ? p4.z : 0u, protect_prev ? p4.w : 0u};
     uint32_t mw[4], cw[4], vw[4] = {0, 0, 0, 0};
     int cm = 0, cc = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         mw[k] = uw[k] & ~rw[k];
-        cw[k] = rw[k] & ~uw[k];
+        cw[k] = rw[k] & ~uw[k] & ~pw[k];
         cm += __popc(mw[k]);
         cc += __popc(cw[k]);
     }
@@ -259,6 +280,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
         rbits4[idx] = make_uint4((rw[0] & ~vw[0]) | mw[0], (rw[1] & ~vw[1]) | mw[1], (rw[2] & ~vw[2]) | mw[2],
                                  (rw[3] & ~vw[3]) | mw[3]);
     if (anyu) ubits4[idx] = make_uint4(0, 0, 0, 0);
+    if (anyu || (p4.x | p4.y | p4.z | p4.w)) pbits4[idx] = u4;     // this batch is the "previous" one next time
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -328,7 +350,7 @@ __global__ __launch_bounds__(256) void k_slots_out(const int32_t* __restrict__ r
 // ---------------------------------------------------------------------------------------------------------
 static int ensure_rbuf(fc_cache* c, int64_t n) {
     if (n <= c->n_cap) return FC_OK;
-    FC_HIP(hipStreamSynchronize(c->stream));
+    FC_HIP(hipDeviceSynchronize());
     if (c->rbuf) FC_HIP(hipFree(c->rbuf));
     c->rbuf = nullptr; c->n_cap = 0;
     const int64_t cap = n + n / 4 + 1024;
@@ -347,7 +369,7 @@ static int ensure_rbuf(fc_cache* c, int64_t n) {
 // link (the store finishes first, the fill catches up) and everything after runs undisturbed.
 // Blocks before the last are stored at once because the one block buffer must be free again for the next gather.
 static int store_block(fc_cache* c, int64_t off, int64_t rows) {
-    FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
+    FC_HIP(hipEventRecord(c->ev_gather_done, c->pst));
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
     FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->vrank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, c->evict_blocks));
     FC_HIP(hipEventRecord(c->ev_evict_done, c->side));
@@ -359,8 +381,8 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
     const int64_t S = c->staging_rows;
     for (int64_t off = 0; off < need; off += S) {
         const int64_t rows = need - off < S ? need - off : S;
-        if (off > 0) FC_HIP(hipStreamWaitEvent(c->stream, c->ev_evict_done, 0));   // block buffer is being read
-        FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        if (off > 0) FC_HIP(hipStreamWaitEvent(c->pst, c->ev_evict_done, 0));   // block buffer is being read
+        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
         if (off + rows >= need && c->evict_early != 1) { *last_off = off; *last_rows = rows; break; }
         FC_TRY(store_block(c, off, rows));
     }
@@ -369,12 +391,12 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
 
 // DMA evict transmitter: wait until every handed-over block is in the host table and drop all transit marks
 // (afterwards the host table alone is current for every non-resident row, and both blocks are free).
-int dma_quiesce(fc_cache* c) {
+int dma_quiesce(fc_cache* c, hipStream_t st) {
     if (!c->dma_evict) return FC_OK;
     pool_wait(c, pool_published(c));
     for (int b = 0; b < 2; ++b) {
         if (c->blk_rows[b] > 0) {
-            k_clear_transit<<<(unsigned)cdiv(c->blk_rows[b], 256), 256, 0, c->stream>>>(c->vrank_buf[b], (int)c->blk_rows[b],
+            k_clear_transit<<<(unsigned)cdiv(c->blk_rows[b], 256), 256, 0, st>>>(c->vrank_buf[b], (int)c->blk_rows[b],
                                                                                        (int)(b * c->staging_rows), c->rank_slot);
             c->blk_rows[b] = 0;
         }
@@ -387,8 +409,8 @@ int dma_quiesce(fc_cache* c) {
 // stream, and let the host threads scatter it once it has landed.  Nothing on the caller's stream waits for it.
 static int evict_dma(fc_cache* c, int64_t need, int buf) {
     float* blk = c->stage_dev + (size_t)buf * c->staging_rows * c->D;
-    FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, blk, nullptr, c->staging_rows, c->cache, c->vslot, c->C, need, 1 << 20));
-    FC_HIP(hipEventRecord(c->ev_gather_done, c->stream));
+    FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, blk, nullptr, c->staging_rows, c->cache, c->vslot, c->C, need, 1 << 20));
+    FC_HIP(hipEventRecord(c->ev_gather_done, c->pst));
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
     {
         ProfScope ps(c, P_D2H_BLOCK, c->side);
@@ -407,12 +429,12 @@ static int evict_staged(fc_cache* c, int64_t need, const int32_t* vrank_host) {
     const size_t rowb = (size_t)c->D * 4;
     for (int64_t off = 0; off < need; off += S) {
         const int64_t rows = need - off < S ? need - off : S;
-        FC_TRY(launch_copy_rows(c, c->stream, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
         {
-            ProfScope ps(c, P_D2H_BLOCK, c->stream);
-            FC_HIP(hipMemcpyAsync(c->stage_pin, c->stage_dev, rows * rowb, hipMemcpyDeviceToHost, c->stream));
+            ProfScope ps(c, P_D2H_BLOCK, c->pst);
+            FC_HIP(hipMemcpyAsync(c->stage_pin, c->stage_dev, rows * rowb, hipMemcpyDeviceToHost, c->pst));
         }
-        FC_HIP(hipStreamSynchronize(c->stream));
+        FC_HIP(hipStreamSynchronize(c->pst));
         float* host = c->host; const float* blk = c->stage_pin; const int32_t* vr = vrank_host + off;
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < rows; ++j) memcpy(host + (size_t)vr[j] * c->D, blk + (size_t)j * c->D, rowb);
@@ -429,27 +451,25 @@ static int fill_staged(fc_cache* c, int64_t M, const int32_t* miss_host) {
 #pragma omp parallel for schedule(static)
         for (int64_t j = 0; j < rows; ++j) memcpy(blk + (size_t)j * c->D, host + (size_t)mr[j] * c->D, rowb);
         {
-            ProfScope ps(c, P_H2D_BLOCK, c->stream);
-            FC_HIP(hipMemcpyAsync(c->stage_dev2, c->stage_pin, rows * rowb, hipMemcpyHostToDevice, c->stream));
+            ProfScope ps(c, P_H2D_BLOCK, c->pst);
+            FC_HIP(hipMemcpyAsync(c->stage_dev2, c->stage_pin, rows * rowb, hipMemcpyHostToDevice, c->pst));
         }
-        FC_TRY(launch_copy_rows(c, c->stream, P_MISS_FILL, c->cache, c->fill_slots + off, c->C, c->stage_dev2, nullptr, c->staging_rows, rows, 1 << 20));
-        FC_HIP(hipStreamSynchronize(c->stream));   // the pinned block is reused by the next round
+        FC_TRY(launch_copy_rows(c, c->pst, P_MISS_FILL, c->cache, c->fill_slots + off, c->C, c->stage_dev2, nullptr, c->staging_rows, rows, 1 << 20));
+        FC_HIP(hipStreamSynchronize(c->pst));   // the pinned block is reused by the next round
     }
     return FC_OK;
 }
 
-int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots) {
+int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
+                 int64_t num_bags, int32_t* slots) {
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!ids || !slots)))
         return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
-    hipStream_t st = c->stream;
+    c->pst = st;
     const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
-    if (c->ps_valid) {                       // a sort nobody used: its scratch buffers must be free before the next one
-        FC_HIP(hipStreamWaitEvent(st, c->ev_sorted, 0));
-        c->ps_valid = false;
-    }
+    const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
     if (c->dma_evict) {
         // the block this call may fill was handed over two blocks ago: its rows must be in the host table by now
@@ -478,7 +498,8 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     }
     {
         ProfScope ps(c, P_RANK_COUNT, st);
-        k_rank_count<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((const uint4*)c->ubits, (const uint4*)c->rbits, c->bsum, (int)c->NB);
+        k_rank_count<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((const uint4*)c->ubits, (const uint4*)c->rbits, (const uint4*)c->pbits,
+                                                            protect_prev, c->bsum, (int)c->NB);
     }
     {
         ProfScope ps(c, P_RANK_PLAN, st);
@@ -492,7 +513,8 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     }
     {
         ProfScope ps(c, P_RANK_EMIT, st);
-        k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, c->ctl, c->moff, c->vtake, c->voff,
+        k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, (uint4*)c->pbits, protect_prev, c->ctl,
+                                                           c->moff, c->vtake, c->voff,
                                                            c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C, transit_base, (int)c->staging_rows);
     }
     FC_HIP(hipGetLastError());
@@ -517,6 +539,9 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
     }
     if (h.status != FC_OK) return h.status;
     const int64_t M = h.n_miss, need = h.need;
+    // Look-ahead: rows about to be evicted or overwritten may still be in use by work the caller enqueued before
+    // this call (the backward pass of the batch before the current one); index decisions above did not care.
+    if (lookahead) FC_HIP(hipStreamWaitEvent(st, c->ev_s_now, 0));
     const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;
     if (staged && (M > 0 || need > 0)) {
         if (M > 0) FC_HIP(hipMemcpyAsync(c->list_pin, c->miss_ranks, (size_t)M * 4, hipMemcpyDeviceToHost, st));
@@ -530,7 +555,7 @@ int prepare_impl(fc_cache* c, const int64_t* ids, int64_t n, const int64_t* offs
         else {
             // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
             // block buffer is reused from its start, so nothing may be in transit in it any more
-            FC_TRY(dma_quiesce(c));
+            FC_TRY(dma_quiesce(c, st));
             FC_TRY(evict_direct(c, need, &last_off, &last_rows));
         }
     }

@@ -103,3 +103,97 @@ def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_eve
     gpu.close()
     orc.close()
     return tot
+
+
+def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows=0, deep_every=1, log=None,
+                         free_running=False):
+    """The look-ahead schedule on both sides: batch t+1 is prepared (protecting batch t's rows) before batch t's
+    forward / backward run.  When the two batches do not fit together both sides must refuse, and the batch is then
+    prepared the plain way after the backward pass.
+    free_running: no device synchronisation inside the loop (the look-ahead stream really runs beside the caller's
+    stream); slots and pooled outputs are kept and compared after the loop."""
+    import torch
+    from oracle import Oracle, OracleError
+    from paper_2208_05321_amd import FreqCache, FreqCacheError
+
+    dev = torch.device("cuda:0")
+    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
+                    warm=False, dma_evict=dma_evict)
+    host_gpu = gpu.host_weight()
+    w.host_table(out=host_gpu)
+    host_orc = host_gpu.copy()
+    if warm:
+        gpu.warm()
+    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm)
+    data = []
+    for t in range(num_batches):
+        ids, offsets = w.batch(t)
+        grad = w.grad(t, len(offsets) - 1)
+        data.append((ids, offsets, grad, torch.from_numpy(ids).to(dev), torch.from_numpy(offsets).to(dev),
+                     torch.from_numpy(grad).to(dev)))
+    torch.cuda.synchronize()
+    so = orc.prepare(data[0][0], data[0][1])
+    sd = gpu.prepare(data[0][3], data[0][4])
+    compare_prepare(gpu, orc, sd.cpu().numpy(), so, 0)
+    tot = {"lookahead": 0, "fallback": 0, "ids": 0, "hit_ids": orc.stats()["n_hit_ids"], "evict": 0}
+    later = []
+    for t in range(num_batches):
+        ids, offsets, grad, ids_d, off_d, grad_d = data[t]
+        so_next = sd_next = None
+        refused = False
+        if t + 1 < num_batches:
+            nids, noff, _, nids_d, noff_d, _ = data[t + 1]
+            try:
+                so_next = orc.prepare(nids, noff, lookahead=True)
+            except OracleError as e:
+                assert e.name == "BATCH_EXCEEDS_CACHE"
+                refused = True
+            try:
+                sd_next = gpu.prepare_next(nids_d, noff_d)
+                assert not refused, f"batch {t + 1}: oracle refused the look-ahead, GPU accepted it"
+            except FreqCacheError as e:
+                assert e.name == "BATCH_EXCEEDS_CACHE" and refused, f"batch {t + 1}: GPU refused ({e.name}), oracle did not"
+            if not refused:
+                if free_running:
+                    assert gpu.stats() == orc.stats(), f"batch {t + 1}: stats"
+                    later.append((f"batch {t + 1}: slots", sd_next, so_next))
+                else:
+                    deep = deep_every and ((t + 1) % deep_every == 0 or t + 2 == num_batches)
+                    compare_prepare(gpu, orc, sd_next.cpu().numpy(), so_next, t + 1, deep=bool(deep))
+                tot["lookahead"] += 1
+        out_d = gpu.embedding_bag_fwd(sd, off_d)
+        out_o = orc.embedding_bag_fwd(so, offsets)
+        if free_running:
+            later.append((f"batch {t}: pooled output", out_d, out_o))
+        else:
+            assert_close(out_d.cpu().numpy(), out_o, f"batch {t}: pooled output")
+        gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
+        orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
+        gpu.advance()
+        if refused:
+            so_next = orc.prepare(nids, noff)
+            sd_next = gpu.prepare(nids_d, noff_d)
+            compare_prepare(gpu, orc, sd_next.cpu().numpy(), so_next, t + 1)
+            tot["fallback"] += 1
+        if t + 1 < num_batches:
+            s = orc.stats()
+            tot["hit_ids"] += s["n_hit_ids"]; tot["evict"] += s["n_evict"]
+        tot["ids"] += len(ids)
+        if log:
+            log(f"  batch {t} ok ({'refused, plain prepare' if refused else 'look-ahead'})")
+        so, sd = so_next, sd_next
+    for what, a, b in later:
+        if a.dtype == torch.int32:
+            assert np.array_equal(a.cpu().numpy(), b), what
+        else:
+            assert_close(a.cpu().numpy(), b, what)
+    assert_close(gpu.rows(), orc.cache, "cached rows at the end")
+    gpu.check()
+    gpu.flush()
+    orc.flush()
+    assert_close(host_gpu, host_orc, "host table after flush")
+    sr, rs = gpu.state()
+    assert np.array_equal(sr, orc.slot_rank) and np.array_equal(rs, orc.rank_slot)
+    gpu.close()
+    orc.close()
+    return tot

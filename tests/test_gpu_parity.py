@@ -4,7 +4,7 @@ import sys
 import numpy as np
 import pytest
 
-from tests.parity import run_parity, assert_close
+from tests.parity import run_parity, run_parity_lookahead, assert_close
 from workloads import make_workload, table_values
 
 pytestmark = pytest.mark.gpu
@@ -102,3 +102,34 @@ def test_dma_evict_rows_come_back_quickly(torch_cuda):
     orc.flush()
     assert_close(gpu.host_weight(), orc.host, "host table")
     gpu.close()
+
+
+@pytest.mark.parametrize("name,scale,ratio,dma", [("c2", 0.1, 0.03, True), ("c2", 0.1, 0.03, False), ("c5", 0.05, 0.03, True),
+                                                  ("c4", 0.01, 0.03, True)])
+def test_lookahead_prepare(torch_cuda, name, scale, ratio, dma):
+    """cache_prepare_next: the next batch is prepared on the library's own stream while the current one trains."""
+    w = make_workload(name, scale=scale, cache_ratio=ratio)
+    tot = run_parity_lookahead(w, 10, warm=True, dma_evict=dma, deep_every=2)
+    assert tot["lookahead"] == 9 and tot["fallback"] == 0 and tot["evict"] > 0
+
+
+def test_lookahead_refused_when_two_batches_do_not_fit(torch_cuda):
+    """1.5% cache at 1/10 scale: one batch fits (12.8k distinct rows of 15k), two do not: both sides refuse the
+    look-ahead and prepare the plain way after the backward pass."""
+    w = make_workload("c2", scale=0.1, cache_ratio=0.015)
+    tot = run_parity_lookahead(w, 6, warm=True, dma_evict=True)
+    assert tot["fallback"] > 0
+
+
+def test_lookahead_cold_start(torch_cuda):
+    w = make_workload("c2", scale=0.05, cache_ratio=0.08)
+    run_parity_lookahead(w, 8, warm=False, dma_evict=True)
+
+
+@pytest.mark.parametrize("dma", [True, False])
+def test_lookahead_free_running(torch_cuda, dma):
+    """No synchronisation inside the loop: the look-ahead stream, the auxiliary sort stream, the side stream and
+    the host scatter threads all run beside the caller's stream; everything is compared after the loop."""
+    w = make_workload("c2", scale=0.2, cache_ratio=0.03)
+    tot = run_parity_lookahead(w, 24, warm=True, dma_evict=dma, free_running=True)
+    assert tot["lookahead"] == 23

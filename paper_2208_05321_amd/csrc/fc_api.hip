@@ -136,6 +136,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }
     if (flags & FC_EVICT_DMA) c->fill_blocks = 48;
     if (const char* e = getenv("FC_FILL_BLOCKS")) { const int v = atoi(e); if (v >= 1) c->fill_blocks = v; }
+    if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
     c->NB = cdiv(cdiv(N, 32), RT_WORDS);
     const size_t words = (size_t)c->NB * RT_WORDS;

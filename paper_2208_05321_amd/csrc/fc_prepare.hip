@@ -45,34 +45,73 @@ __global__ __launch_bounds__(MARK_THREADS) void k_remap_mark(const int64_t* __re
     const int64_t end = begin + per_block < work ? begin + per_block : work;
     int hits = 0;
     uint32_t flags = 0;
-    for (int64_t i = begin + tid; i < end; i += MARK_THREADS) {
-        if (i < n) {
-            const int64_t id = ids[i];
-            int r = -1;
-            if (id < 0 || id >= N) {
-                flags |= EF_ID_RANGE;
-            } else {
-                r = freq_rank[id];
-                const uint32_t w = (uint32_t)r >> 5, bit = 1u << (r & 31);
-                if (w < (uint32_t)lds_words) atomicOr(&low[w], bit);
-                // rare ranks: bits are only ever set during this kernel, so a read that sees the bit is final
-                else if (!(ubits[w] & bit)) atomicOr(&ubits[w], bit);
-                hits += (rbits[w] & bit) != 0;
-            }
-            rbuf[i] = r;
+    // four ids per thread and round: all loads of a stage are issued before any of them is waited for
+    for (int64_t i0 = begin + tid; i0 < end; i0 += 4 * MARK_THREADS) {
+        int64_t id[4];
+        int r[4];
+        uint32_t rb[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t i = i0 + (int64_t)k * MARK_THREADS;
+            id[k] = (i < end && i < n) ? ids[i] : 0;
         }
-        if (i <= num_bags) {
-            const int64_t o = offsets[i];
-            if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
-            if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
-            if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t i = i0 + (int64_t)k * MARK_THREADS;
+            r[k] = -1;
+            if (i < end && i < n) {
+                if (id[k] < 0 || id[k] >= N) flags |= EF_ID_RANGE;
+                else r[k] = freq_rank[id[k]];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) rb[k] = r[k] >= 0 ? rbits[(uint32_t)r[k] >> 5] : 0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t i = i0 + (int64_t)k * MARK_THREADS;
+            if (i < end && i < n) {
+                if (r[k] >= 0) {
+                    const uint32_t w = (uint32_t)r[k] >> 5, bit = 1u << (r[k] & 31);
+                    if (w < (uint32_t)lds_words) atomicOr(&low[w], bit);
+                    // rare ranks: bits are only ever set during this kernel, so a read that sees the bit is final
+                    else if (!(ubits[w] & bit)) atomicOr(&ubits[w], bit);
+                    hits += (rb[k] & bit) != 0;
+                }
+                rbuf[i] = r[k];
+            }
+            if (i < end && i <= num_bags) {
+                const int64_t o = offsets[i];
+                if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
+                if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
+                if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
+            }
         }
     }
     __syncthreads();
-    for (int w = tid; w < lds_words; w += MARK_THREADS) {
-        const uint32_t v = low[w];
-        if (v && (v & ~ubits[w])) atomicOr(&ubits[w], v);
+    // Merge into the global bitmap: LDS words first, then all global reads at once, then the atomics still needed.
+    // Every workgroup holds the hottest words, so each starts at a different word: by the time most of them reach a
+    // hot word its bits are already set and the (coherent) read spares the atomic.
+    const int rot = (int)(((int64_t)blockIdx.x * lds_words) / gridDim.x);
+    constexpr int FL = MARK_LDS_WORDS / MARK_THREADS;
+    uint32_t v[FL], g[FL];
+    int wi[FL];
+#pragma unroll
+    for (int k = 0; k < FL; ++k) {
+        int w = k * MARK_THREADS + tid;
+        v[k] = 0;
+        if (w < lds_words) {
+            w += rot;
+            if (w >= lds_words) w -= lds_words;
+            v[k] = low[w];
+        }
+        wi[k] = w;
     }
+#pragma unroll
+    for (int k = 0; k < FL; ++k)
+        g[k] = v[k] ? __hip_atomic_load(&ubits[wi[k]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xFFFFFFFFu;
+#pragma unroll
+    for (int k = 0; k < FL; ++k)
+        if (v[k] & ~g[k]) atomicOr(&ubits[wi[k]], v[k]);
     hits = wave_sum(hits);
     if ((tid & 63) == 0) red[tid >> 6] = hits;
     __syncthreads();
@@ -485,7 +524,7 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
         transit_base = (int)(buf * c->staging_rows);
     }
     const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
-    int64_t nmark = cdiv(work, 4 * MARK_THREADS);
+    int64_t nmark = cdiv(work, (int64_t)c->mark_ids_per_thread * MARK_THREADS);
     if (nmark > MARK_MAX_BLOCKS) nmark = MARK_MAX_BLOCKS;
     const int64_t per_block = cdiv(cdiv(work, nmark), MARK_THREADS) * MARK_THREADS;
     nmark = cdiv(work, per_block);

@@ -31,11 +31,13 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
+def _load(path: str | None = None):
+    """The oracle library (built on demand); `path` loads another build of it (used by the mutation tests)."""
     global _lib
-    if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+    if _lib is None or path is not None:
+        if path is None:
+            build()
+        L = ctypes.CDLL(path or _LIB)
         vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
         L.fco_create.argtypes = [i64, i32, i64, vp, vp, i32, ctypes.POINTER(vp)]
         L.fco_create.restype = ctypes.c_int
@@ -57,6 +59,8 @@ def _load():
                      "fco_evict_slots", "fco_fill_slots"):
             getattr(L, name).argtypes = [vp]
             getattr(L, name).restype = vp
+        if path is not None:
+            return L
         _lib = L
     return _lib
 
@@ -68,8 +72,8 @@ class Oracle:
     """Owns the oracle's cached weight and maps; `host` (fp32 [N, D], rank-ordered) is the caller's array
     and is updated in place by evictions and flush."""
 
-    def __init__(self, freq_rank: np.ndarray, host: np.ndarray, cache_rows: int, warm: bool = True):
-        L = _load()
+    def __init__(self, freq_rank: np.ndarray, host: np.ndarray, cache_rows: int, warm: bool = True, lib=None):
+        L = lib if lib is not None else _load()
         self._L = L
         self.freq_rank = np.ascontiguousarray(freq_rank, dtype=np.int32)
         assert host.dtype == np.float32 and host.flags.c_contiguous and host.ndim == 2

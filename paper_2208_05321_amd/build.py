@@ -17,9 +17,9 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, extra_flags=(), out: str | None = None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    cmd = [hipcc, *FLAGS, *extra_flags, *[os.path.join(CSRC, s) for s in SOURCES], "-o", out or LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -29,7 +29,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":

@@ -149,13 +149,13 @@ __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ 
             bool open_left = prevk == cur;
             first_kind = 0; has_head = 0; head_slot = -1;
             V acc = vzero(V());
-            for (int e0 = 0; e0 < cnt; e0 += 8) {
-                V g[8];
+            for (int e0 = 0; e0 < cnt; e0 += BWD_PF) {
+                V g[BWD_PF];
 #pragma unroll
-                for (int k = 0; k < 8; ++k)      // eight independent row loads in flight
+                for (int k = 0; k < BWD_PF; ++k)  // BWD_PF independent row loads in flight
                     g[k] = e0 + k < cnt ? reinterpret_cast<const V*>(grad + (size_t)mv[e0 + k] * D)[cidx] : vzero(V());
 #pragma unroll
-                for (int k = 0; k < 8; ++k) {
+                for (int k = 0; k < BWD_PF; ++k) {
                     if (e0 + k < cnt) {
                         const int kk = mk[e0 + k];
                         if (kk != cur) {              // run of `cur` ends inside the chunk

@@ -20,7 +20,15 @@ constexpr int RS_ITEMS = 16;
 constexpr int RS_TILE = RS_THREADS * RS_ITEMS;
 constexpr int RS_MAX_BITS = 11;
 // Consecutive sorted lookups reduced by one row-group in the backward pass.
-constexpr int BWD_CHUNK = 32;
+#ifndef FC_BWD_CHUNK
+#define FC_BWD_CHUNK 32
+#endif
+#ifndef FC_BWD_PF
+#define FC_BWD_PF 8
+#endif
+constexpr int BWD_CHUNK = FC_BWD_CHUNK;
+// Gradient rows a row-group keeps in flight while it walks its chunk.
+constexpr int BWD_PF = FC_BWD_PF;
 
 // Sticky device-side flags.
 enum : uint32_t { EF_BAD_OFFSETS = 1u, EF_ID_RANGE = 2u, EF_BAD_SLOT = 4u };

@@ -84,6 +84,9 @@ def main():
                     help="dma: misses read by kernels from the mapped host table, evicted blocks leave by DMA and are "
                          "scattered by host threads (default); direct: kernels both ways, no host threads; "
                          "staged: the paper's gather / bulk copy / scatter both ways")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="issue cache_plan_next(t+1) beside batch t's forward/backward and move rows at cache_advance (same "
+                         "results; pays off when the step is HBM-bound, e.g. config 4, not when it is link-bound)")
     ap.add_argument("--lookahead", action="store_true",
                     help="prepare batch t+1 with cache_prepare_next before batch t's forward/backward (a different cache "
                          "policy: the previous batch's rows are protected too; not the headline configuration)")
@@ -183,7 +186,22 @@ def main():
             cache.prepare(ids_d[t + 1], off_d[t + 1], out=nxt)
             stats.append(cache.stats())
 
-    step = step_lookahead if args.lookahead else step_plain
+    def step_planned(t):
+        # same policy and results as step_plain; the index half of batch t+1's prepare is issued before batch t's
+        # forward / backward and runs beside them on the library's stream, its rows move at cache_advance
+        cur = slots2[t & 1][: n_ids[t]]
+        if t == 0:
+            cache.prepare(ids_d[0], off_d[0], out=cur)
+            stats.append(cache.stats())
+        nxt = slots2[(t + 1) & 1][: n_ids[t + 1]]
+        cache.embedding_bag_fwd(cur, off_d[t], out=out)
+        cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
+        cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels run beside the two calls above
+        stats.append(cache.stats())
+        cache.advance()
+
+    pipelined = args.pipeline and not args.lookahead and args.transmitter != "staged"
+    step = step_lookahead if args.lookahead else (step_planned if pipelined else step_plain)
 
     for t in range(args.warmup):
         step(t)
@@ -306,6 +324,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_features} features in one {w.num_rows} x {w.dim} fp32 table, "
                                f"batch {w.samples} x {w.num_features} {'multi-hot' if w.multi_hot else 'one-hot'} ids, "
                                f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
+                   "schedule": "fwd(t), bwd(t) enqueued; cache_plan_next(t+1) beside them; cache_advance" if pipelined else
+                               ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if args.lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
                    "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if args.lookahead else "Algorithm 1 as printed",
                    "transmitter": {"dma": "kernel miss fill + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),
                                    "direct": "kernels both ways", "staged": "block transmitter both ways"}[args.transmitter],

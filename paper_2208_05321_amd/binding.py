@@ -23,7 +23,7 @@ STAT_FIELDS = ("n_ids", "n_unique", "n_hit_unique", "n_hit_ids", "n_miss", "n_ev
 
 # every symbol include/freqcache.h declares
 EXPORTS = (
-    "cache_create", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
+    "cache_create", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_plan_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
     "cache_check", "cache_destroy", "cache_last_stats", "cache_copy_state", "cache_last_lists", "cache_copy_rows",
     "cache_host_weight", "cache_strerror", "cache_profile_enable", "cache_profile_count", "cache_profile_name",
     "cache_profile_get", "freq_create", "freq_add", "freq_build", "freq_destroy", "table_reorder",
@@ -55,6 +55,7 @@ def load_library(path: str | None = None):
     L.cache_warm.argtypes = [vp]
     L.cache_prepare.argtypes = [vp, vp, i64, vp, i64, vp]
     L.cache_prepare_next.argtypes = [vp, vp, i64, vp, i64, vp]
+    L.cache_plan_next.argtypes = [vp, vp, i64, vp, i64, vp]
     L.cache_advance.argtypes = [vp]
     L.embedding_bag_fwd.argtypes = [vp, vp, i64, vp, i64, vp]
     L.embedding_bag_bwd_sgd.argtypes = [vp, vp, i64, vp, i64, vp, ctypes.c_float]
@@ -167,6 +168,16 @@ class FreqCache:
         slots = out if out is not None else torch.empty(n, dtype=torch.int32, device=ids.device)
         rc = self._L.cache_prepare_next(self._h, _ptr(ids), n, _ptr(offsets), offsets.numel() - 1, _ptr(slots))
         self._check(rc, "cache_prepare_next")
+        return slots
+
+    def plan_next(self, ids, offsets, out=None):
+        """cache_plan_next: index half of cache_prepare for the next batch, ahead of time; rows move at advance()."""
+        torch = self._torch
+        n = ids.numel()
+        assert ids.dtype == torch.int64 and offsets.dtype == torch.int64 and ids.is_cuda and offsets.is_cuda
+        slots = out if out is not None else torch.empty(n, dtype=torch.int32, device=ids.device)
+        rc = self._L.cache_plan_next(self._h, _ptr(ids), n, _ptr(offsets), offsets.numel() - 1, _ptr(slots))
+        self._check(rc, "cache_plan_next")
         return slots
 
     def advance(self):

@@ -70,6 +70,7 @@ static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
     for (hipStream_t x : {c->pre, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
+    c->planned.valid = false; c->last_index_stream = c->last_move_stream = nullptr;
     for (PresortRec& r : c->rec) r.valid = false;
     if (c->dma_evict) { pool_wait(c, pool_published(c)); c->blk_rows[0] = c->blk_rows[1] = 0; }
     const int64_t words = c->NB * RT_WORDS;
@@ -114,7 +115,7 @@ static void destroy(fc_cache* c) {
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_s_now, c->ev_pre_done}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->aux) (void)hipStreamDestroy(c->aux);
     if (c->pre) (void)hipStreamDestroy(c->pre);
@@ -203,7 +204,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done,
+    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done,
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
@@ -221,6 +222,11 @@ using namespace fc;
 
 // the caller's stream takes over from the look-ahead stream: everything cache_prepare_next enqueued comes first
 static int adopt_next(fc_cache* c) {
+    if (c->planned.valid) {            // a batch planned ahead whose rows have not moved yet: move them now
+        const MovePlan mv = c->planned;
+        c->planned.valid = false;
+        FC_TRY(prepare_move(c, c->stream, mv));
+    }
     if (c->next_pending || c->last_pst != c->stream) {
         FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));
         c->next_pending = false;
@@ -301,9 +307,28 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
     return FC_OK;
 }
 
+int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
+                    int32_t* slots_dev) {
+    if (!c || (c->flags & FC_TRANSMIT_STAGED)) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    if (c->planned.valid) FC_TRY(adopt_next(c));
+    FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
+    if (c->last_pst != c->pre) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
+    MovePlan mv;
+    const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv);
+    c->pst = c->stream;
+    FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
+    c->last_pst = c->pre;
+    c->next_pending = true;
+    if (rc != FC_OK) return rc;
+    c->planned = mv;
+    return FC_OK;
+}
+
 int cache_advance(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    if (c->planned.valid) return adopt_next(c);
     if (c->next_pending) {
         FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));
         c->next_pending = false;

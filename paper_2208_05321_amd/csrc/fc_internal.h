@@ -64,6 +64,8 @@ struct SortBufs {
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr, *ghist = nullptr, *dtot = nullptr;
     int64_t cap = 0, ghist_cap = 0;
 };
+// What the row-movement half of a cache_prepare has to do (decided by the index half).
+struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0; };
 struct PresortRec {
     bool valid = false;
     const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
@@ -84,8 +86,10 @@ struct fc_cache {
     // Look-ahead (cache_prepare_next): the next batch is prepared on `pre` while the caller's stream still trains on
     // the current one.  pst = the stream the cache_prepare / cache_prepare_next in progress enqueues on.
     hipStream_t pre = nullptr, pst = nullptr, last_pst = nullptr;
-    hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr;
+    hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr, ev_index_done = nullptr, ev_move_done = nullptr;
+    hipStream_t last_index_stream = nullptr, last_move_stream = nullptr;
     bool next_pending = false;
+    fc::MovePlan planned;           // cache_plan_next: row movement still to be done by cache_advance
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
     bool evict_pending = false;
@@ -199,6 +203,9 @@ void prof_collect(fc_cache* c);
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // entry points implemented across the sources
+int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
+                  int64_t num_bags, int32_t* slots, MovePlan* mv);
+int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv);
 int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
                  int64_t num_bags, int32_t* slots);
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);

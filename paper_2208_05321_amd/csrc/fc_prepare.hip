@@ -499,14 +499,19 @@ static int fill_staged(fc_cache* c, int64_t M, const int32_t* miss_host) {
     return FC_OK;
 }
 
-int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
-                 int64_t num_bags, int32_t* slots) {
+// Index half of Algorithm 1: every decision (unique rows, misses, victims, slot assignment, both maps, the slots
+// of the batch) and no row movement.  Fills *mv with what prepare_move has to do.
+int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
+                  int64_t num_bags, int32_t* slots, MovePlan* mv) {
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!ids || !slots)))
         return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     c->pst = st;
+    // the lists this call rewrites (missing ranks, victims, fill slots) may still be read by the previous batch's
+    // row movement if that ran on another stream
+    if (c->last_move_stream && c->last_move_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_move_done, 0));
     const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
     const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
@@ -578,26 +583,6 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
     }
     if (h.status != FC_OK) return h.status;
     const int64_t M = h.n_miss, need = h.need;
-    // Look-ahead: rows about to be evicted or overwritten may still be in use by work the caller enqueued before
-    // this call (the backward pass of the batch before the current one); index decisions above did not care.
-    if (lookahead) FC_HIP(hipStreamWaitEvent(st, c->ev_s_now, 0));
-    const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;
-    if (staged && (M > 0 || need > 0)) {
-        if (M > 0) FC_HIP(hipMemcpyAsync(c->list_pin, c->miss_ranks, (size_t)M * 4, hipMemcpyDeviceToHost, st));
-        if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
-        FC_HIP(hipStreamSynchronize(st));
-    }
-    int64_t last_off = 0, last_rows = 0;
-    if (need > 0) {
-        if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
-        else if (c->dma_evict && need <= c->staging_rows) FC_TRY(evict_dma(c, need, buf));
-        else {
-            // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
-            // block buffer is reused from its start, so nothing may be in transit in it any more
-            FC_TRY(dma_quiesce(c, st));
-            FC_TRY(evict_direct(c, need, &last_off, &last_rows));
-        }
-    }
     if (M > 0) {
         {
             const unsigned tiles = (unsigned)cdiv(c->C, FREE_TILE);
@@ -610,7 +595,7 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
                                                       c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
         // every row of the batch has its slot now: write the slots out and start sorting them for the backward
-        // pass on the auxiliary stream, while the missing rows cross the host link
+        // pass on the auxiliary stream (it will run while the missing rows cross the host link)
         if (n > 0) {
             {
                 ProfScope ps(c, P_SLOTS_OUT, st);
@@ -618,13 +603,6 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
             }
             (void)presort_impl(c, slots, n, offsets, num_bags);   // on failure the backward pass sorts (and reports) itself
         }
-        if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
-            FC_TRY(store_block(c, last_off, last_rows));
-            last_rows = -1;
-        }
-        if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
-        else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
-        else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
     }
     if (M == 0 && n > 0) {
         {
@@ -633,9 +611,10 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
         }
         (void)presort_impl(c, slots, n, offsets, num_bags);
     }
-    if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
-    if (last_rows < 0) { FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0)); c->evict_pending = false; }
     FC_HIP(hipGetLastError());
+    FC_HIP(hipEventRecord(c->ev_index_done, st));
+    c->last_index_stream = st;
+    mv->valid = true; mv->M = M; mv->need = need; mv->buf = buf;
     c->last.n_ids = n;
     c->last.n_unique = h.n_unique;
     c->last.n_hit_unique = h.n_unique - M;
@@ -646,6 +625,55 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
     c->last.bytes_d2h = need * (int64_t)c->D * 4;
     c->have_lists = true;
     return FC_OK;
+}
+
+// Row-movement half: evicted rows out (gather, then DMA block / kernel store / staged copy), missing rows in.
+int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
+    c->pst = st;
+    if (c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_index_done, 0));
+    const int64_t M = mv.M, need = mv.need;
+    const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;
+    if (staged && (M > 0 || need > 0)) {
+        if (M > 0) FC_HIP(hipMemcpyAsync(c->list_pin, c->miss_ranks, (size_t)M * 4, hipMemcpyDeviceToHost, st));
+        if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
+        FC_HIP(hipStreamSynchronize(st));
+    }
+    int64_t last_off = 0, last_rows = 0;
+    if (need > 0) {
+        if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
+        else if (c->dma_evict && need <= c->staging_rows) FC_TRY(evict_dma(c, need, mv.buf));
+        else {
+            // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
+            // block buffer is reused from its start, so nothing may be in transit in it any more
+            FC_TRY(dma_quiesce(c, st));
+            FC_TRY(evict_direct(c, need, &last_off, &last_rows));
+        }
+    }
+    if (M > 0) {
+        if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
+            FC_TRY(store_block(c, last_off, last_rows));
+            last_rows = -1;
+        }
+        if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
+        else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
+        else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
+    }
+    if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
+    if (last_rows < 0) { FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0)); c->evict_pending = false; }
+    FC_HIP(hipGetLastError());
+    FC_HIP(hipEventRecord(c->ev_move_done, st));
+    c->last_move_stream = st;
+    return FC_OK;
+}
+
+int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
+                 int64_t num_bags, int32_t* slots) {
+    MovePlan mv;
+    FC_TRY(prepare_index(c, st, lookahead, ids, n, offsets, num_bags, slots, &mv));
+    // Look-ahead: rows about to be evicted or overwritten may still be in use by work the caller enqueued before
+    // this call (the backward pass of the batch before the current one); the index decisions did not care.
+    if (lookahead) FC_HIP(hipStreamWaitEvent(st, c->ev_s_now, 0));
+    return prepare_move(c, st, mv);
 }
 
 }  // namespace fc

@@ -197,3 +197,76 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
     gpu.close()
     orc.close()
     return tot
+
+
+def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0, free_running=False, plan_first=False):
+    """cache_plan_next: the index half of the next batch's prepare runs beside the current batch's forward / backward,
+    rows move at cache_advance.  Same policy as plain cache_prepare, so the oracle is simply driven in program order."""
+    import torch
+    from oracle import Oracle
+    from paper_2208_05321_amd import FreqCache
+
+    dev = torch.device("cuda:0")
+    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
+                    warm=False, dma_evict=dma_evict)
+    host_gpu = gpu.host_weight()
+    w.host_table(out=host_gpu)
+    host_orc = host_gpu.copy()
+    if warm:
+        gpu.warm()
+    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm)
+    data = []
+    for t in range(num_batches):
+        ids, offsets = w.batch(t)
+        grad = w.grad(t, len(offsets) - 1)
+        data.append((ids, offsets, grad, torch.from_numpy(ids).to(dev), torch.from_numpy(offsets).to(dev),
+                     torch.from_numpy(grad).to(dev)))
+    torch.cuda.synchronize()
+    so = orc.prepare(data[0][0], data[0][1])
+    sd = gpu.prepare(data[0][3], data[0][4])
+    compare_prepare(gpu, orc, sd.cpu().numpy(), so, 0)
+    later = []
+    for t in range(num_batches):
+        ids, offsets, grad, ids_d, off_d, grad_d = data[t]
+        def plan():
+            nxt = gpu.plan_next(data[t + 1][3], data[t + 1][4]) if t + 1 < num_batches else None
+            return nxt, gpu.stats(), (None if free_running or nxt is None else gpu.last_lists())
+        if plan_first:          # both call orders are legal
+            sd_next, gstats, glists = plan()
+        out_d = gpu.embedding_bag_fwd(sd, off_d)
+        gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
+        if not plan_first:
+            sd_next, gstats, glists = plan()
+        gpu.advance()
+        out_o = orc.embedding_bag_fwd(so, offsets)
+        orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
+        if free_running:
+            later.append((f"batch {t}: pooled output", out_d, out_o))
+        else:
+            assert_close(out_d.cpu().numpy(), out_o, f"batch {t}: pooled output")
+        if sd_next is not None:
+            so_next = orc.prepare(data[t + 1][0], data[t + 1][1])
+            assert gstats == orc.stats(), f"batch {t + 1}: stats {gstats} vs {orc.stats()}"
+            if free_running:
+                later.append((f"batch {t + 1}: slots", sd_next, so_next))
+            else:
+                lo = orc.last_lists()
+                assert np.array_equal(glists["miss_ranks"], lo["miss_ranks"]) and np.array_equal(glists["fill_slots"], lo["fill_slots"])
+                assert np.array_equal(np.sort(glists["evict_ranks"]), np.sort(lo["evict_ranks"]))
+                compare_prepare(gpu, orc, sd_next.cpu().numpy(), so_next, t + 1)
+                assert_close(gpu.rows(), orc.cache, f"batch {t + 1}: cached rows after the rows moved")
+            so, sd = so_next, sd_next
+    for what, a, b in later:
+        if a.dtype == torch.int32:
+            assert np.array_equal(a.cpu().numpy(), b), what
+        else:
+            assert_close(a.cpu().numpy(), b, what)
+    assert_close(gpu.rows(), orc.cache, "cached rows at the end")
+    gpu.check()
+    gpu.flush()
+    orc.flush()
+    assert_close(host_gpu, host_orc, "host table after flush")
+    sr, rs = gpu.state()
+    assert np.array_equal(sr, orc.slot_rank) and np.array_equal(rs, orc.rank_slot)
+    gpu.close()
+    orc.close()

@@ -4,7 +4,7 @@ import sys
 import numpy as np
 import pytest
 
-from tests.parity import run_parity, run_parity_lookahead, assert_close
+from tests.parity import run_parity, run_parity_lookahead, run_parity_planned, assert_close
 from workloads import make_workload, table_values
 
 pytestmark = pytest.mark.gpu
@@ -133,3 +133,45 @@ def test_lookahead_free_running(torch_cuda, dma):
     w = make_workload("c2", scale=0.2, cache_ratio=0.03)
     tot = run_parity_lookahead(w, 24, warm=True, dma_evict=dma, free_running=True)
     assert tot["lookahead"] == 23
+
+
+@pytest.mark.parametrize("name,scale,ratio,dma,free", [
+    ("c2", 0.1, 0.015, True, False), ("c2", 0.1, 0.015, False, False), ("c5", 0.05, 0.015, True, False),
+    ("c2", 0.2, 0.015, True, True), ("c2", 0.2, 0.015, False, True), ("c4", 0.02, 0.03, True, True),
+])
+def test_planned_prepare(torch_cuda, name, scale, ratio, dma, free):
+    """cache_plan_next + cache_advance: index work of batch t+1 beside the forward / backward of batch t; identical
+    results to plain cache_prepare (same oracle, program order)."""
+    w = make_workload(name, scale=scale, cache_ratio=ratio)
+    run_parity_planned(w, 16 if free else 8, warm=True, dma_evict=dma, free_running=free)
+    run_parity_planned(w, 6, warm=True, dma_evict=dma, free_running=free, plan_first=True)
+
+
+def test_planned_prepare_cold_and_small_blocks(torch_cuda):
+    w = make_workload("c2", scale=0.05, cache_ratio=0.05)
+    run_parity_planned(w, 8, warm=False, dma_evict=True, staging_rows=900)     # some batches exceed one block
+    run_parity_planned(w, 6, warm=False, dma_evict=False, staging_rows=5)
+
+
+def test_planned_then_plain_prepare_and_flush(torch_cuda):
+    """A planned batch that is never advanced explicitly: the next plain call (or flush) moves its rows first."""
+    import torch
+    from tests.test_gpu_edge import make_pair
+    w = make_workload("c2", scale=0.05, cache_ratio=0.03)
+    gpu, orc = make_pair(w, warm=True, dma_evict=True)
+    dev = torch.device("cuda:0")
+    dt = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    b = [w.batch(t) for t in range(4)]
+    s0 = gpu.prepare(dt(b[0][0]), dt(b[0][1])); orc.prepare(*b[0])
+    s1 = gpu.plan_next(dt(b[1][0]), dt(b[1][1]))                  # planned ...
+    so1 = orc.prepare(*b[1])
+    s2 = gpu.prepare(dt(b[2][0]), dt(b[2][1]))                    # ... and overtaken by a plain prepare
+    so2 = orc.prepare(*b[2])
+    assert np.array_equal(s1.cpu().numpy(), so1) and np.array_equal(s2.cpu().numpy(), so2)
+    assert_close(gpu.rows(), orc.cache, "rows after plan + plain prepare")
+    gpu.plan_next(dt(b[3][0]), dt(b[3][1]))
+    orc.prepare(*b[3])
+    gpu.flush(); orc.flush()                                       # flush completes the planned batch first
+    assert_close(gpu.host_weight(), orc.host, "host table")
+    assert_close(gpu.rows(), orc.cache, "rows")
+    gpu.close()

@@ -194,10 +194,10 @@ def main():
             cache.prepare(ids_d[0], off_d[0], out=cur)
             stats.append(cache.stats())
         nxt = slots2[(t + 1) & 1][: n_ids[t + 1]]
+        cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels run while batch t's rows still arrive
+        stats.append(cache.stats())
         cache.embedding_bag_fwd(cur, off_d[t], out=out)
         cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
-        cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels run beside the two calls above
-        stats.append(cache.stats())
         cache.advance()
 
     pipelined = args.pipeline and not args.lookahead and args.transmitter != "staged"
@@ -324,7 +324,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_features} features in one {w.num_rows} x {w.dim} fp32 table, "
                                f"batch {w.samples} x {w.num_features} {'multi-hot' if w.multi_hot else 'one-hot'} ids, "
                                f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
-                   "schedule": "fwd(t), bwd(t) enqueued; cache_plan_next(t+1) beside them; cache_advance" if pipelined else
+                   "schedule": "cache_plan_next(t+1) beside the arrival of batch t's rows | fwd(t), bwd(t) | cache_advance" if pipelined else
                                ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if args.lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
                    "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if args.lookahead else "Algorithm 1 as printed",
                    "transmitter": {"dma": "kernel miss fill + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),

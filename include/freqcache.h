@@ -138,16 +138,20 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
                        int32_t* slots_dev);
 /* Software pipelining WITHOUT a change of policy: the index half of cache_prepare for the NEXT batch (ids -> ranks,
  * unique rows, misses, victims, slot assignment, the slots of the batch, the sort for its backward pass), enqueued on
- * a library-owned stream while the caller's stream still runs the current batch's forward / backward.  None of these
- * decisions depends on embedding values, so the results (slots, statistics, lists, maps) are exactly those of
- * cache_prepare called after the current batch's backward pass.  No row is moved: cache_advance does that, on the
- * caller's stream, i.e. after the backward pass the caller enqueued in between.
- * Same arguments and errors as cache_prepare; not available with FC_TRANSMIT_STAGED.  ids_dev / offsets_dev must be
- * complete when the call is made and stay untouched until cache_advance; cache_copy_rows / cache_host_weight reflect
- * the planned batch only after cache_advance.
- * Usage:  cache_prepare(batch 0);  loop { fwd(t); bwd(t); cache_plan_next(batch t+1, slots_next); cache_advance(); }
- * (forward / backward are asynchronous, so they are best enqueued first: cache_plan_next waits on the host for its
- * planning kernels, which then run beside them; calling it before them is equally correct.) */
+ * a library-owned stream beside whatever the caller's stream still runs for the current batch: the arrival of its
+ * missing rows, its forward and its backward pass.  None of these decisions depends on embedding values, so the
+ * results (slots, statistics, lists, maps) are exactly those of cache_prepare called after the current batch's
+ * backward pass.  No row is moved: cache_advance does that, on the caller's stream, i.e. after the backward pass the
+ * caller enqueued in between.
+ * Same arguments and errors as cache_prepare; not available with FC_TRANSMIT_STAGED.
+ * Ordering: the index work is ordered behind the caller's stream as of the ENTRY of the latest cache_prepare /
+ * cache_advance call, not as of this call.  ids_dev / offsets_dev must therefore be complete by then (written by work
+ * enqueued on the caller's stream before that call, or finished altogether) and stay untouched until cache_advance;
+ * slots_dev must not be the buffer the current batch's forward / backward read.  cache_copy_rows / cache_host_weight
+ * reflect the planned batch only after cache_advance.
+ * Usage:  cache_prepare(batch 0);  loop { cache_plan_next(batch t+1, slots_next); fwd(t); bwd(t); cache_advance(); }
+ * (the call waits on the host for its planning kernels, which run while the rows of batch t are still arriving;
+ * calling it after fwd / bwd is equally correct.) */
 int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                     int32_t* slots_dev);
 /* Makes the batch of the latest cache_prepare_next / cache_plan_next the current one (for cache_plan_next this is

@@ -43,9 +43,6 @@ void prof_collect(fc_cache* c) {
 }
 
 // ---- state initialisation ----
-__global__ void k_fill_i32(int32_t* p, int64_t n, int32_t v) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
-}
 // first `count` entries: identity, rest -1
 __global__ void k_iota_or_neg(int32_t* p, int64_t n, int64_t count) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -62,7 +59,7 @@ __global__ void k_bits_prefix(uint32_t* p, int64_t words, int64_t count) {
     }
 }
 __global__ void k_set_ctl(Ctl* ctl, int nfree) {
-    ctl->err_flags = 0; ctl->async_flags = 0; ctl->hit_ids = 0; ctl->nfree = nfree;
+    ctl->err_flags = 0; ctl->async_flags = 0; ctl->nfree = nfree;
     ctl->status = 0; ctl->n_unique = 0; ctl->n_miss = 0; ctl->need = 0;
 }
 
@@ -70,7 +67,7 @@ static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
     for (hipStream_t x : {c->pre, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
-    c->planned.valid = false; c->last_index_stream = c->last_move_stream = nullptr;
+    c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr;
     for (PresortRec& r : c->rec) r.valid = false;
     if (c->dma_evict) { pool_wait(c, pool_published(c)); c->blk_rows[0] = c->blk_rows[1] = 0; }
     const int64_t words = c->NB * RT_WORDS;
@@ -94,17 +91,16 @@ static void destroy(fc_cache* c) {
     (void)hipSetDevice(c->device);
     if (c->stream || c->side) (void)hipDeviceSynchronize();
     pool_destroy(c);
-    if (c->dma_evict) c->vrank = nullptr;      // points into vrank_buf
     for (int b = 0; b < 2; ++b) {
         if (c->blk_pin[b]) (void)hipHostFree(c->blk_pin[b]);
         if (c->vrank_pin[b]) (void)hipHostFree(c->vrank_pin[b]);
         if (c->vrank_buf[b]) (void)hipFree(c->vrank_buf[b]);
         if (c->ev_d2h[b]) (void)hipEventDestroy(c->ev_d2h[b]);
     }
-    if (c->fill_src) (void)hipFree(c->fill_src);
+    for (auto& set : c->lists) for (int32_t* p : set) if (p) (void)hipFree(p);
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
                     (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
-                    (void*)c->miss_ranks, (void*)c->vrank, (void*)c->vslot, (void*)c->fill_slots, (void*)c->rbuf,
+                    (void*)c->rbuf,
                     (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->part, (void*)c->pmeta, (void*)c->pbits})
         if (p) (void)hipFree(p);
     for (SortBufs& sb : c->sb)
@@ -115,7 +111,7 @@ static void destroy(fc_cache* c) {
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_plan, c->ev_evict_done, c->ev_gather_done, c->ev_tmp, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->aux) (void)hipStreamDestroy(c->aux);
     if (c->pre) (void)hipStreamDestroy(c->pre);
@@ -170,8 +166,10 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipMalloc((void**)&c->moff, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->vtake, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->voff, (size_t)c->NB * 4));
-    FC_HIP(hipMalloc((void**)&c->miss_ranks, (size_t)C * 4));
     c->dma_evict = (flags & FC_EVICT_DMA) != 0;
+    for (auto& set : c->lists)
+        for (int k = 0; k < 5; ++k)
+            if (k < 3 || (k == 3 ? c->dma_evict : !c->dma_evict)) FC_HIP(hipMalloc((void**)&set[k], (size_t)C * 4));
     if (c->dma_evict) {
         for (int b = 0; b < 2; ++b) {
             FC_HIP(hipMalloc((void**)&c->vrank_buf[b], (size_t)C * 4));
@@ -181,13 +179,8 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
             }
             FC_HIP(hipEventCreateWithFlags(&c->ev_d2h[b], hipEventDisableTiming | hipEventBlockingSync));
         }
-        FC_HIP(hipMalloc((void**)&c->fill_src, (size_t)C * 4));
-        c->vrank = c->vrank_buf[0];
-    } else {
-        FC_HIP(hipMalloc((void**)&c->vrank, (size_t)C * 4));
     }
-    FC_HIP(hipMalloc((void**)&c->vslot, (size_t)C * 4));
-    FC_HIP(hipMalloc((void**)&c->fill_slots, (size_t)C * 4));
+    use_list_set(c, 0);
     FC_HIP(hipMalloc((void**)&c->ctl, sizeof(Ctl)));
     FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4 * (c->dma_evict ? 2 : 1)));
     if (hipHostMalloc((void**)&c->hctl, sizeof(HostCtl), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_OOM_PINNED; }
@@ -204,7 +197,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_plan, &c->ev_evict_done, &c->ev_gather_done, &c->ev_tmp, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done,
+    for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
@@ -280,6 +273,7 @@ int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t*
                   int32_t* slots_dev) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
     FC_TRY(adopt_next(c));
     return prepare_impl(c, c->stream, false, ids_dev, n, offsets_dev, num_bags, slots_dev);
 }
@@ -311,9 +305,11 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
                     int32_t* slots_dev) {
     if (!c || (c->flags & FC_TRANSMIT_STAGED)) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
-    if (c->planned.valid) FC_TRY(adopt_next(c));
-    FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
-    if (c->last_pst != c->pre) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
+    if (c->planned.valid) FC_TRY(cache_advance(c));
+    // The index half touches no rows, so it need not wait for the row movement, forward or backward work the caller
+    // enqueued since the last cache_prepare / cache_advance: it is ordered behind the caller's stream as of the entry
+    // of that call (which covers the backward pass whose sorted pairs this call's sort will overwrite).
+    FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
     MovePlan mv;
     const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv);
     c->pst = c->stream;
@@ -328,6 +324,7 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
 int cache_advance(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
+    FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
     if (c->planned.valid) return adopt_next(c);
     if (c->next_pending) {
         FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));

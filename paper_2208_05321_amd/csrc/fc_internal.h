@@ -37,7 +37,6 @@ enum : uint32_t { EF_BAD_OFFSETS = 1u, EF_ID_RANGE = 2u, EF_BAD_SLOT = 4u };
 struct Ctl {
     uint32_t err_flags;     // EF_* raised by the current cache_prepare
     uint32_t async_flags;   // EF_BAD_SLOT raised by fwd / bwd kernels
-    int32_t hit_ids;        // ids whose row was resident before this batch
     int32_t nfree;          // empty slots
     int32_t status;         // FC_* decision of the current cache_prepare
     int32_t n_unique, n_miss, need;
@@ -86,12 +85,18 @@ struct fc_cache {
     // Look-ahead (cache_prepare_next): the next batch is prepared on `pre` while the caller's stream still trains on
     // the current one.  pst = the stream the cache_prepare / cache_prepare_next in progress enqueues on.
     hipStream_t pre = nullptr, pst = nullptr, last_pst = nullptr;
-    hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr, ev_index_done = nullptr, ev_move_done = nullptr;
-    hipStream_t last_index_stream = nullptr, last_move_stream = nullptr;
+    hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr, ev_index_done = nullptr;
+    hipStream_t last_index_stream = nullptr;
+    // The lists an index half writes and its row-movement half reads exist twice, so that the index half of the next
+    // batch can run while the rows of the current one still move: lset = the set of the latest index half.
+    int lset = 0;
+    int32_t* lists[2][5] = {};      // per set: miss_ranks, vslot, fill_slots, fill_src, vrank (vrank: kernel-store transmitters only)
+    hipEvent_t ev_move_done[2] = {nullptr, nullptr};   // the row movement that read set k has finished
+    hipStream_t move_stream[2] = {nullptr, nullptr};   // the stream it ran on (nullptr: none yet)
     bool next_pending = false;
     fc::MovePlan planned;           // cache_plan_next: row movement still to be done by cache_advance
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
-    hipEvent_t ev_plan = nullptr, ev_evict_done = nullptr, ev_gather_done = nullptr, ev_tmp = nullptr;
+    hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
@@ -117,10 +122,11 @@ struct fc_cache {
     int32_t* moff = nullptr;        // [NB] output offset of a tile's missing ranks
     int32_t* vtake = nullptr;       // [NB] victims taken from a tile
     int32_t* voff = nullptr;        // [NB] output offset of a tile's victims
-    int32_t* miss_ranks = nullptr;  // [C]
+    int32_t* miss_ranks = nullptr;  // [C]  these five point into lists[lset] (vrank into vrank_buf with FC_EVICT_DMA)
     int32_t* vrank = nullptr;       // [C]
     int32_t* vslot = nullptr;       // [C]
     int32_t* fill_slots = nullptr;  // [C]
+    int32_t* fill_src = nullptr;    // [C]  FC_EVICT_DMA: where each missing row is read from (-1 host, <= -2 transit)
     int32_t* rbuf = nullptr;        // [n_cap] rank of every input id
     int64_t n_cap = 0;
     fc::Ctl* ctl = nullptr;
@@ -142,7 +148,6 @@ struct fc_cache {
     int32_t* vrank_buf[2] = {nullptr, nullptr};   // device lists of the evicted ranks, one per block
     int64_t blk_rows[2] = {0, 0};                 // rows whose transit marks are still set, per block
     hipEvent_t ev_d2h[2] = {nullptr, nullptr};
-    int32_t* fill_src = nullptr;                  // [C] where each missing row is read from (-1 host, <= -2 transit)
     uint64_t dma_seq = 0;                         // blocks handed to the pool so far
 
     float* host = nullptr;          // pinned, rank-ordered table
@@ -175,6 +180,13 @@ struct fc_cache {
 };
 
 namespace fc {
+
+// make list set k the current one (with FC_EVICT_DMA the victim ranks live with their block, not with the set)
+inline void use_list_set(fc_cache* c, int k) {
+    c->lset = k;
+    c->miss_ranks = c->lists[k][0]; c->vslot = c->lists[k][1]; c->fill_slots = c->lists[k][2]; c->fill_src = c->lists[k][3];
+    if (!c->dma_evict) c->vrank = c->lists[k][4];
+}
 
 // ---- error plumbing ----
 #define FC_HIP(expr)                                   \

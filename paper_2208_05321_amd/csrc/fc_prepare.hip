@@ -226,7 +226,6 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
         const int nf = status == FC_OK ? nfree + need - M : nfree;
         ctl->nfree = nf;
         ctl->err_flags = 0;
-        ctl->hit_ids = 0;
         hctl->status = status; hctl->n_unique = totU; hctl->n_miss = M; hctl->need = need;
         hctl->hit_ids = hits; hctl->nfree = nf; hctl->async_flags = (int32_t)ctl->async_flags;
         __threadfence_system();                       // the record first, then the ticket the host is polling for
@@ -509,9 +508,12 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     FC_HIP(hipSetDevice(c->device));
     FC_TRY(ensure_rbuf(c, n));
     c->pst = st;
-    // the lists this call rewrites (missing ranks, victims, fill slots) may still be read by the previous batch's
-    // row movement if that ran on another stream
-    if (c->last_move_stream && c->last_move_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_move_done, 0));
+    // the list set this call rewrites (missing ranks, victims, fill slots) was last read by the row movement two
+    // batches back, possibly on another stream
+    use_list_set(c, c->lset ^ 1);
+    c->have_lists = false;
+    if (c->move_stream[c->lset] && c->move_stream[c->lset] != st) FC_HIP(hipStreamWaitEvent(st, c->ev_move_done[c->lset], 0));
+    if (c->last_index_stream && c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_index_done, 0));
     const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
     const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
@@ -661,8 +663,8 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     if (last_rows > 0) FC_TRY(store_block(c, last_off, last_rows));
     if (last_rows < 0) { FC_HIP(hipStreamWaitEvent(st, c->ev_evict_done, 0)); c->evict_pending = false; }
     FC_HIP(hipGetLastError());
-    FC_HIP(hipEventRecord(c->ev_move_done, st));
-    c->last_move_stream = st;
+    FC_HIP(hipEventRecord(c->ev_move_done[c->lset], st));
+    c->move_stream[c->lset] = st;
     return FC_OK;
 }
 

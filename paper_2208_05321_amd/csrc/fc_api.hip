@@ -13,7 +13,7 @@ namespace fc {
 static const char* const kProfNames[P_COUNT] = {
     "remap_mark", "rank_count", "rank_plan", "rank_emit", "evict_gather", "evict_store", "free_count", "free_assign",
     "miss_fill", "slots_out", "bag_fwd", "sort_hist", "sort_scan", "sort_scatter", "bwd_reduce", "bwd_fixup",
-    "h2d_block", "d2h_block", "flush_rows"};
+    "h2d_block", "d2h_block", "flush_rows", "rows_in"};
 
 ProfScope::ProfScope(fc_cache* c_, int item_, hipStream_t s_) : c(c_), s(s_), item(item_) {
     if (!c || !c->prof_on) return;
@@ -65,11 +65,11 @@ __global__ void k_set_ctl(Ctl* ctl, int nfree) {
 
 static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
-    for (hipStream_t x : {c->pre, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
+    for (hipStream_t x : {c->pre, c->pf, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
-    c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr;
+    c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr; c->pf_dep = nullptr;
     for (PresortRec& r : c->rec) r.valid = false;
-    if (c->dma_evict) { pool_wait(c, pool_published(c)); c->blk_rows[0] = c->blk_rows[1] = 0; }
+    if (c->dma_evict) { pool_wait(c, pool_published(c)); for (int64_t& r : c->blk_rows) r = 0; }
     const int64_t words = c->NB * RT_WORDS;
     k_iota_or_neg<<<1024, 256, 0, st>>>(c->rank_slot, c->N, warm ? c->C : 0);
     k_iota_or_neg<<<256, 256, 0, st>>>(c->slot_rank, c->C, warm ? c->C : 0);
@@ -91,13 +91,17 @@ static void destroy(fc_cache* c) {
     (void)hipSetDevice(c->device);
     if (c->stream || c->side) (void)hipDeviceSynchronize();
     pool_destroy(c);
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < DMA_BLOCKS; ++b) {
         if (c->blk_pin[b]) (void)hipHostFree(c->blk_pin[b]);
         if (c->vrank_pin[b]) (void)hipHostFree(c->vrank_pin[b]);
         if (c->vrank_buf[b]) (void)hipFree(c->vrank_buf[b]);
         if (c->ev_d2h[b]) (void)hipEventDestroy(c->ev_d2h[b]);
     }
     for (auto& set : c->lists) for (int32_t* p : set) if (p) (void)hipFree(p);
+    for (int k = 0; k < 2; ++k) {
+        if (c->arrive[k]) (void)hipFree(c->arrive[k]);
+        if (c->ev_arrive[k]) (void)hipEventDestroy(c->ev_arrive[k]);
+    }
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
                     (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
                     (void*)c->rbuf,
@@ -115,6 +119,7 @@ static void destroy(fc_cache* c) {
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->aux) (void)hipStreamDestroy(c->aux);
     if (c->pre) (void)hipStreamDestroy(c->pre);
+    if (c->pf) (void)hipStreamDestroy(c->pf);
     delete c;
 }
 
@@ -133,6 +138,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }
     if (flags & FC_EVICT_DMA) c->fill_blocks = 48;
     if (const char* e = getenv("FC_FILL_BLOCKS")) { const int v = atoi(e); if (v >= 1) c->fill_blocks = v; }
+    if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
     c->NB = cdiv(cdiv(N, 32), RT_WORDS);
@@ -171,7 +177,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
         for (int k = 0; k < 5; ++k)
             if (k < 3 || (k == 3 ? c->dma_evict : !c->dma_evict)) FC_HIP(hipMalloc((void**)&set[k], (size_t)C * 4));
     if (c->dma_evict) {
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < DMA_BLOCKS; ++b) {
             FC_HIP(hipMalloc((void**)&c->vrank_buf[b], (size_t)C * 4));
             if (hipHostMalloc((void**)&c->blk_pin[b], (size_t)staging_rows * D * 4, hipHostMallocDefault) != hipSuccess ||
                 hipHostMalloc((void**)&c->vrank_pin[b], (size_t)staging_rows * 4, hipHostMallocDefault) != hipSuccess) {
@@ -182,7 +188,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     }
     use_list_set(c, 0);
     FC_HIP(hipMalloc((void**)&c->ctl, sizeof(Ctl)));
-    FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4 * (c->dma_evict ? 2 : 1)));
+    FC_HIP(hipMalloc((void**)&c->stage_dev, (size_t)staging_rows * D * 4 * (c->dma_evict ? DMA_BLOCKS : 1)));
     if (hipHostMalloc((void**)&c->hctl, sizeof(HostCtl), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_OOM_PINNED; }
     memset(c->hctl, 0, sizeof(HostCtl));
     if (flags & FC_TRANSMIT_STAGED) {
@@ -195,9 +201,10 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
     FC_HIP(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
     FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
+    FC_HIP(hipStreamCreateWithFlags(&c->pf, hipStreamNonBlocking));
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1],
+    for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
@@ -317,7 +324,24 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     c->last_pst = c->pre;
     c->next_pending = true;
     if (rc != FC_OK) return rc;
+    // Missing rows ahead of time: they are not resident, so nothing the caller's stream still does to the current
+    // batch changes them; their newest copy is in the host table or in an evicted-row block (transit marks), and the
+    // latest row movement, which produced both, is the only thing to wait for.  Victims leave, and these rows enter
+    // their slots, at cache_advance.
     c->planned = mv;
+    if (mv.M > 0 && mv.M <= c->staging_rows) {
+        const int k = c->lset;
+        if (!c->arrive[k] && hipMalloc((void**)&c->arrive[k], (size_t)c->staging_rows * c->D * 4) != hipSuccess) {
+            (void)hipGetLastError(); c->arrive[k] = nullptr;
+            return FC_OK;                  // no room for the block: the rows are fetched at cache_advance instead
+        }
+        FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
+        if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
+        if (c->dma_evict) FC_TRY(launch_fill_rows(c, c->pf, mv.M, c->arrive[k], c->staging_rows, c->fill_blocks_early));
+        else FC_TRY(launch_copy_rows(c, c->pf, P_MISS_FILL, c->arrive[k], nullptr, c->staging_rows, c->host_dev, c->miss_ranks, c->N, mv.M, c->fill_blocks));
+        FC_HIP(hipEventRecord(c->ev_arrive[k], c->pf));
+        c->planned.arrived = true;
+    }
     return FC_OK;
 }
 

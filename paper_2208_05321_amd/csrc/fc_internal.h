@@ -51,7 +51,7 @@ struct HostCtl {
 enum ProfItem {
     P_REMAP_MARK = 0, P_RANK_COUNT, P_RANK_PLAN, P_RANK_EMIT, P_EVICT_GATHER, P_EVICT_STORE, P_FREE_COUNT, P_FREE_PICK,
     P_MISS_FILL, P_SLOTS_OUT, P_BAG_FWD, P_SORT_HIST, P_SORT_SCAN, P_SORT_SCATTER, P_BWD_REDUCE, P_BWD_FIXUP,
-    P_H2D_BLOCK, P_D2H_BLOCK, P_FLUSH_ROWS, P_COUNT
+    P_H2D_BLOCK, P_D2H_BLOCK, P_FLUSH_ROWS, P_ROWS_IN, P_COUNT
 };
 
 struct ProfSpan { int item; hipEvent_t a, b; };
@@ -64,7 +64,9 @@ struct SortBufs {
     int64_t cap = 0, ghist_cap = 0;
 };
 // What the row-movement half of a cache_prepare has to do (decided by the index half).
-struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0; };
+// evicted-row blocks of the DMA evict transmitter that may be on their way at once
+constexpr int DMA_BLOCKS = 4;
+struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0; bool arrived = false; };
 struct PresortRec {
     bool valid = false;
     const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
@@ -93,6 +95,12 @@ struct fc_cache {
     int32_t* lists[2][5] = {};      // per set: miss_ranks, vslot, fill_slots, fill_src, vrank (vrank: kernel-store transmitters only)
     hipEvent_t ev_move_done[2] = {nullptr, nullptr};   // the row movement that read set k has finished
     hipStream_t move_stream[2] = {nullptr, nullptr};   // the stream it ran on (nullptr: none yet)
+    // cache_plan_next also fetches the planned batch's missing rows ahead of time, on the stream `pf`, into the
+    // arrival block of its list set (row j of the block = j-th missing rank); cache_advance then only copies them
+    // from HBM into their slots.  Allocated by the first cache_plan_next.
+    hipStream_t pf = nullptr;
+    float* arrive[2] = {nullptr, nullptr};             // [staging_rows][D] each
+    hipEvent_t ev_arrive[2] = {nullptr, nullptr};
     bool next_pending = false;
     fc::MovePlan planned;           // cache_plan_next: row movement still to be done by cache_advance
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
@@ -101,6 +109,7 @@ struct fc_cache {
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
                                     // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through
+    int fill_blocks_early = 60;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
     int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
     int evict_early = 2;            // when that kernel starts (tuning: FC_EVICT_EARLY): 0 after the miss fill, under
                                     // forward/backward; 1 right after the gather; 2 together with the miss fill
@@ -138,16 +147,17 @@ struct fc_cache {
     int32_t* list_pin = nullptr;    // staged mode: pinned copies of miss / victim rank lists [2*C]
 
     // DMA evict transmitter (FC_EVICT_DMA): evicted-row blocks leave HBM by hipMemcpyAsync on the side stream and
-    // are scattered into the host table by worker threads; two blocks in flight.  While a row's newest copy is
+    // are scattered into the host table by worker threads; up to DMA_BLOCKS blocks in flight.  While a row's newest copy is
     // still on its way, rank_slot[rank] = -2 - (block * staging_rows + row in block) ("in transit") and a miss
     // on it is served from the device-side block instead of the host table.
     bool dma_evict = false;
     fc::ScatterPool* pool = nullptr;
-    float* blk_pin[2] = {nullptr, nullptr};       // pinned landing blocks
-    int32_t* vrank_pin[2] = {nullptr, nullptr};   // pinned copies of the evicted ranks
-    int32_t* vrank_buf[2] = {nullptr, nullptr};   // device lists of the evicted ranks, one per block
-    int64_t blk_rows[2] = {0, 0};                 // rows whose transit marks are still set, per block
-    hipEvent_t ev_d2h[2] = {nullptr, nullptr};
+    float* blk_pin[fc::DMA_BLOCKS] = {};          // pinned landing blocks
+    int32_t* vrank_pin[fc::DMA_BLOCKS] = {};      // pinned copies of the evicted ranks
+    int32_t* vrank_buf[fc::DMA_BLOCKS] = {};      // device lists of the evicted ranks, one per block
+    int64_t blk_rows[fc::DMA_BLOCKS] = {};        // rows whose transit marks are still set, per block
+    hipEvent_t ev_d2h[fc::DMA_BLOCKS] = {};
+    hipEvent_t pf_dep = nullptr;                  // what the next early fetch of missing rows has to wait for
     uint64_t dma_seq = 0;                         // blocks handed to the pool so far
 
     float* host = nullptr;          // pinned, rank-ordered table
@@ -233,7 +243,8 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
 // host[slot_rank[s]] = cache[s] for every resident slot, written straight into the mapped host table.
 int launch_flush_rows(fc_cache* c, hipStream_t s);
 // miss fill that honours transit marks: row j comes from the host table or from a device-side evicted-row block
-int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows);
+// dst == nullptr: into the cache slots fill_slots[j]; else into row j of the block dst (of dst_rows rows)
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst = nullptr, int64_t dst_rows = 0, int max_blocks = 0);
 
 // scatter pool (fc_worker.hip)
 int pool_create(fc_cache* c, int threads);

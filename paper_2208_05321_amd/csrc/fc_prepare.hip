@@ -432,7 +432,7 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
 int dma_quiesce(fc_cache* c, hipStream_t st) {
     if (!c->dma_evict) return FC_OK;
     pool_wait(c, pool_published(c));
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < DMA_BLOCKS; ++b) {
         if (c->blk_rows[b] > 0) {
             k_clear_transit<<<(unsigned)cdiv(c->blk_rows[b], 256), 256, 0, st>>>(c->vrank_buf[b], (int)c->blk_rows[b],
                                                                                        (int)(b * c->staging_rows), c->rank_slot);
@@ -518,10 +518,10 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
     if (c->dma_evict) {
-        // the block this call may fill was handed over two blocks ago: its rows must be in the host table by now
+        // the block this call may fill was handed over DMA_BLOCKS blocks ago: its rows must be in the host table by now
         const uint64_t seq = pool_published(c) + 1;
-        buf = (int)(seq & 1);
-        if (seq > 2) pool_wait(c, seq - 2);
+        buf = (int)(seq % DMA_BLOCKS);
+        if (seq > DMA_BLOCKS) pool_wait(c, seq - DMA_BLOCKS);
         if (c->blk_rows[buf] > 0) {
             k_clear_transit<<<(unsigned)cdiv(c->blk_rows[buf], 256), 256, 0, st>>>(c->vrank_buf[buf], (int)c->blk_rows[buf],
                                                                                 (int)(buf * c->staging_rows), c->rank_slot);
@@ -641,22 +641,30 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
         FC_HIP(hipStreamSynchronize(st));
     }
     int64_t last_off = 0, last_rows = 0;
+    // Rows fetched ahead of time (cache_plan_next) were read from the host table and from evicted-row blocks other
+    // than the one this batch's victims go to (its marks were dropped before this batch was indexed), so the
+    // victims need not wait for them; a kernel-store evict reuses the block buffer from its start and has to.
+    bool arrival_waited = !mv.arrived;
+    bool dma_path = false;
     if (need > 0) {
         if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
-        else if (c->dma_evict && need <= c->staging_rows) FC_TRY(evict_dma(c, need, mv.buf));
+        else if (c->dma_evict && need <= c->staging_rows) { FC_TRY(evict_dma(c, need, mv.buf)); dma_path = true; }
         else {
             // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
             // block buffer is reused from its start, so nothing may be in transit in it any more
+            if (!arrival_waited) { FC_HIP(hipStreamWaitEvent(st, c->ev_arrive[c->lset], 0)); arrival_waited = true; }
             FC_TRY(dma_quiesce(c, st));
             FC_TRY(evict_direct(c, need, &last_off, &last_rows));
         }
-    }
+    } else if (c->dma_evict) dma_path = true;
     if (M > 0) {
         if (last_rows > 0 && c->evict_early == 2) {       // store and fill share the link, then the link falls silent
             FC_TRY(store_block(c, last_off, last_rows));
             last_rows = -1;
         }
+        if (!arrival_waited) FC_HIP(hipStreamWaitEvent(st, c->ev_arrive[c->lset], 0));
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
+        else if (mv.arrived) FC_TRY(launch_copy_rows(c, st, P_ROWS_IN, c->cache, c->fill_slots, c->C, c->arrive[c->lset], nullptr, c->staging_rows, M, 1 << 20));
         else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
     }
@@ -665,6 +673,11 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     FC_HIP(hipGetLastError());
     FC_HIP(hipEventRecord(c->ev_move_done[c->lset], st));
     c->move_stream[c->lset] = st;
+    // The next early fetch reads evicted-row blocks gathered up to now and host rows stored up to now: with the DMA
+    // transmitter the gather just enqueued is the last thing it needs (host rows still on their way carry transit
+    // marks); after a kernel store it has to wait for the whole movement.
+    if (!dma_path) c->pf_dep = c->ev_move_done[c->lset];
+    else if (need > 0) c->pf_dep = c->ev_gather_done;
     return FC_OK;
 }
 

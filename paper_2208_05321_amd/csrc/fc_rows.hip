@@ -52,8 +52,9 @@ __global__ __launch_bounds__(256) void k_flush_rows(float* __restrict__ host, co
     }
 }
 
-// Miss fill of the DMA evict transmitter: row j goes to slot fill_slots[j]; it comes from the host table, or, if
-// its newest copy is still in transit (fill_src[j] <= -2), from the evicted-row block that holds it.
+// Miss fill of the DMA evict transmitter: row j goes to slot fill_slots[j] (to row j if there is no such list); it
+// comes from the host table, or, if its newest copy is still in transit (fill_src[j] <= -2), from the evicted-row
+// block that holds it.
 template <int VEC>
 __global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, const int32_t* __restrict__ fill_slots,
                                                    unsigned C, const float* __restrict__ host,
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, co
     const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
     const int nv = D / VEC;
     for (int j = blockIdx.x * gpb + gl; j < rows; j += gridDim.x * gpb) {
-        const int di = fill_slots[j];
+        const int di = fill_slots ? fill_slots[j] : j;
         const int code = fill_src[j];
         const float* srow;
         if (code <= -2) {
@@ -108,16 +109,18 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
     return FC_OK;
 }
 
-int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows) {
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst, int64_t dst_rows, int max_blocks) {
     if (rows <= 0) return FC_OK;
     const int sh = shift_of(c->lpr);
     const int gpb = 256 >> sh;
     int64_t blocks = cdiv(rows, gpb);
-    if (blocks > c->fill_blocks) blocks = c->fill_blocks;
+    if (max_blocks <= 0) max_blocks = c->fill_blocks;
+    if (blocks > max_blocks) blocks = max_blocks;
     ProfScope ps(c, P_MISS_FILL, s);
 #define FC_FILL(V) \
-    k_fill_rows<V><<<(unsigned)blocks, 256, 0, s>>>(c->cache, c->fill_slots, (unsigned)c->C, c->host_dev, c->miss_ranks, (unsigned)c->N, \
-                                                    c->stage_dev, c->fill_src, (unsigned)(2 * c->staging_rows), (int)rows, c->D, sh)
+    k_fill_rows<V><<<(unsigned)blocks, 256, 0, s>>>(dst ? dst : c->cache, dst ? nullptr : c->fill_slots, (unsigned)(dst ? dst_rows : c->C), \
+                                                    c->host_dev, c->miss_ranks, (unsigned)c->N, \
+                                                    c->stage_dev, c->fill_src, (unsigned)(DMA_BLOCKS * c->staging_rows), (int)rows, c->D, sh)
     switch (c->vec) { case 4: FC_FILL(4); break; case 2: FC_FILL(2); break; default: FC_FILL(1); break; }
 #undef FC_FILL
     FC_HIP(hipGetLastError());

@@ -1,8 +1,8 @@
 // Host side of the DMA evict transmitter: a small pool of threads that scatters evicted-row blocks, once their
 // device -> host copy has landed in pinned memory, into the frequency-ordered host table
 // (paper Section 4.3, data transmitter: "blocks are transferred ... and scattered to the corresponding position
-// of the target memory").  Blocks are numbered 1, 2, ... in hand-over order and finished in that order, so a row
-// evicted twice ends with its newer value.
+// of the target memory").  Blocks are numbered 1, 2, ... in hand-over order and scattered one after the other, so a
+// row evicted twice ends with its newer value.
 #include "fc_internal.h"
 
 #include <atomic>
@@ -19,8 +19,8 @@ struct ScatterPool {
     std::mutex m;
     std::condition_variable cv_job, cv_done;
     uint64_t published = 0, completed = 0;
-    struct Job { int buf; int64_t rows; } jobs[2] = {};
-    std::atomic<int> remaining[2];
+    struct Job { int buf; int64_t rows; } jobs[DMA_BLOCKS] = {};
+    std::atomic<int> remaining[DMA_BLOCKS];
     bool stop = false;
 };
 
@@ -33,7 +33,10 @@ static void worker(fc_cache* c, ScatterPool* p, int k, int K) {
             std::unique_lock<std::mutex> lk(p->m);
             p->cv_job.wait(lk, [&] { return p->stop || p->published >= next; });
             if (p->published < next) return;       // stop requested and nothing left to do
-            j = p->jobs[next & 1];
+            j = p->jobs[next % DMA_BLOCKS];
+            // blocks land strictly one after the other: a row evicted again two batches later must not be
+            // overtaken by its older copy in the hands of a slower thread
+            p->cv_done.wait(lk, [&] { return p->completed + 1 >= next; });
         }
         (void)hipEventSynchronize(c->ev_d2h[j.buf]);   // the block and its rank list are in pinned memory
         const int64_t a = j.rows * k / K, b = j.rows * (k + 1) / K;
@@ -41,7 +44,7 @@ static void worker(fc_cache* c, ScatterPool* p, int k, int K) {
         const int32_t* vr = c->vrank_pin[j.buf];
         float* host = c->host;
         for (int64_t r = a; r < b; ++r) memcpy(host + (size_t)vr[r] * c->D, blk + (size_t)r * c->D, rowb);
-        if (p->remaining[next & 1].fetch_sub(1) == 1) {
+        if (p->remaining[next % DMA_BLOCKS].fetch_sub(1) == 1) {
             std::lock_guard<std::mutex> lk(p->m);
             p->completed = next;
             p->cv_done.notify_all();
@@ -52,7 +55,7 @@ static void worker(fc_cache* c, ScatterPool* p, int k, int K) {
 int pool_create(fc_cache* c, int threads) {
     ScatterPool* p = new (std::nothrow) ScatterPool();
     if (!p) return FC_ERR_INVALID_ARG;
-    p->remaining[0] = 0; p->remaining[1] = 0;
+    for (auto& r : p->remaining) r = 0;
     c->pool = p;
     try {
         for (int k = 0; k < threads; ++k) p->threads.emplace_back(worker, c, p, k, threads);
@@ -80,8 +83,8 @@ void pool_publish(fc_cache* c, int buf, int64_t rows) {
     ScatterPool* p = c->pool;
     std::lock_guard<std::mutex> lk(p->m);
     const uint64_t seq = p->published + 1;
-    p->jobs[seq & 1] = {buf, rows};
-    p->remaining[seq & 1] = (int)p->threads.size();
+    p->jobs[seq % DMA_BLOCKS] = {buf, rows};
+    p->remaining[seq % DMA_BLOCKS] = (int)p->threads.size();
     p->published = seq;
     p->cv_job.notify_all();
 }

@@ -84,12 +84,12 @@ def main():
                     help="dma: misses read by kernels from the mapped host table, evicted blocks leave by DMA and are "
                          "scattered by host threads (default); direct: kernels both ways, no host threads; "
                          "staged: the paper's gather / bulk copy / scatter both ways")
-    ap.add_argument("--pipeline", action="store_true",
-                    help="issue cache_plan_next(t+1) beside batch t's forward/backward and move rows at cache_advance (same "
-                         "results; pays off when the step is HBM-bound, e.g. config 4, not when it is link-bound)")
-    ap.add_argument("--lookahead", action="store_true",
-                    help="prepare batch t+1 with cache_prepare_next before batch t's forward/backward (a different cache "
-                         "policy: the previous batch's rows are protected too; not the headline configuration)")
+    ap.add_argument("--schedule", choices=("pipelined", "plain", "lookahead"), default="pipelined",
+                    help="pipelined (default): fwd(t), bwd(t), cache_plan_next(t+1), cache_advance - Algorithm 1 as printed, the "
+                         "index kernels and the row fetch of batch t+1 run on library streams beside batch t (identical results); "
+                         "plain: cache_prepare(t), fwd(t), bwd(t), everything on one stream; "
+                         "lookahead: cache_prepare_next(t+1) before fwd(t), bwd(t) - a different cache policy (the previous "
+                         "batch's rows are protected too), not the headline configuration")
     ap.add_argument("--static-module", action="store_true",
                     help="instead of the per-batch path, time the GPU build of the static module (id counting + ranking)")
     ap.add_argument("--staging-rows", type=int, default=0)
@@ -131,7 +131,7 @@ def main():
 
     # inputs resident in HBM before the timed region
     ids_d, off_d, n_ids = [], [], []
-    for t in range(total_steps + P + 1):
+    for t in range(total_steps + 2 * P + 1):
         ids, offsets = w.batch(t)
         ids_d.append(torch.from_numpy(ids).to(dev))
         off_d.append(torch.from_numpy(offsets).to(dev))
@@ -141,7 +141,7 @@ def main():
     max_n = max(n_ids)
     slots = torch.empty(max_n, dtype=torch.int32, device=dev)
     out = torch.empty((nb, w.dim), dtype=torch.float32, device=dev)
-    log(f"[bench] {total_steps + P} batches on device ({time.time() - t0:.1f}s)")
+    log(f"[bench] {total_steps + 2 * P + 1} batches on device ({time.time() - t0:.1f}s)")
 
     if args.calib_copy_mb > 0:
         a = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device=dev)
@@ -194,14 +194,16 @@ def main():
             cache.prepare(ids_d[0], off_d[0], out=cur)
             stats.append(cache.stats())
         nxt = slots2[(t + 1) & 1][: n_ids[t + 1]]
-        cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels run while batch t's rows still arrive
-        stats.append(cache.stats())
-        cache.embedding_bag_fwd(cur, off_d[t], out=out)
+        cache.embedding_bag_fwd(cur, off_d[t], out=out)           # enqueued first: they wait on the GPU for batch t's rows
         cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
+        cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels and row fetch of batch t+1 run beside all that
+        stats.append(cache.stats())
         cache.advance()
 
-    pipelined = args.pipeline and not args.lookahead and args.transmitter != "staged"
-    step = step_lookahead if args.lookahead else (step_planned if pipelined else step_plain)
+    if args.schedule == "pipelined" and args.transmitter == "staged":
+        args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter
+    pipelined, lookahead = args.schedule == "pipelined", args.schedule == "lookahead"
+    step = step_lookahead if lookahead else (step_planned if pipelined else step_plain)
 
     for t in range(args.warmup):
         step(t)
@@ -227,46 +229,53 @@ def main():
     roofline = None
     host_link = None
     if args.profile_steps > 0:
-        # P further batches of the same trace, each kernel / copy bracketed by HIP events
-        cache.profile(True)
-        pstats = []
-        for t in range(total_steps, total_steps + P):
-            step(t)
-            pstats.append(stats[-1])
-        rep = cache.profile_report()
-        cache.profile(False)
         R = w.dim * 4
-        n_m = float(np.mean([s["n_ids"] for s in pstats]))
-        u_m = float(np.mean([s["n_unique"] for s in pstats]))
-        m_m = float(np.mean([s["n_miss"] for s in pstats]))
-        e_m = float(np.mean([s["n_evict"] for s in pstats]))
         nw = -(-w.num_rows // 32)
-        # algorithmic bytes per launch (what the step must move, "byte model")
-        model = {
-            "remap_mark": n_m * (8 + 4 + 4 + 4) + (nb + 1) * 8,            # id, idx_map entry, resident bit word, rank out
-            "rank_count": nw * 4 * 2,
-            "rank_emit": nw * 4 * 2 + m_m * 4 + e_m * (8 + 4 + 4),
-            "evict_gather": e_m * (2 * R + 4),
-            "evict_store": e_m * (2 * R + 4),
-            "free_count": w.cache_rows * 4, "free_assign": w.cache_rows * 4 + m_m * 16,
-            "miss_fill": m_m * (2 * R + 8),
-            "slots_out": n_m * 12,
-            "bag_fwd": n_m * (R + 4) + nb * (R + 8),
-            "bwd_reduce": n_m * 8 + nb * R + 2 * u_m * R,                  # grad read once per bag (one-hot: per id)
-            "sort_hist": n_m * 4, "sort_scatter": n_m * 16,
-        }
-        if w.multi_hot:
-            model["bwd_reduce"] = n_m * 8 + n_m * R + 2 * u_m * R        # every lookup reads its bag's gradient row
-        for name, r in rep.items():
-            avg_us = r["ms"] / r["launches"] * 1e3
-            launches_per_step = r["launches"] / P
-            k = {"avg_us": round(avg_us, 2), "launches_per_step": round(launches_per_step, 2),
-                 "us_per_step": round(avg_us * launches_per_step, 2)}
-            if name in model:
-                per_launch = model[name] / max(launches_per_step, 1e-9)
-                k["alg_bytes_per_launch"] = int(per_launch)
-                k["alg_GBps"] = round(per_launch / (avg_us * 1e-6) / 1e9, 1)
-            kernels[name] = k
+
+        def profile_pass(step_fn, first):
+            """P further batches of the same trace, each kernel / copy bracketed by HIP events on its own stream."""
+            cache.profile(True)
+            pstats = []
+            for t in range(first, first + P):
+                step_fn(t)
+                pstats.append(stats[-1])
+            rep = cache.profile_report()
+            cache.profile(False)
+            n_m = float(np.mean([s["n_ids"] for s in pstats]))
+            u_m = float(np.mean([s["n_unique"] for s in pstats]))
+            m_m = float(np.mean([s["n_miss"] for s in pstats]))
+            e_m = float(np.mean([s["n_evict"] for s in pstats]))
+            # algorithmic bytes per launch (what the step must move; DESIGN.md, "byte model")
+            model = {
+                "remap_mark": n_m * (8 + 4 + 4 + 4) + (nb + 1) * 8,            # id, idx_map entry, resident bit word, rank out
+                "rank_count": nw * 4 * 2,
+                "rank_emit": nw * 4 * 2 + m_m * 4 + e_m * (8 + 4 + 4),
+                "evict_gather": e_m * (2 * R + 4),
+                "evict_store": e_m * (2 * R + 4),
+                "free_count": w.cache_rows * 4, "free_assign": w.cache_rows * 4 + m_m * 16,
+                "miss_fill": m_m * (2 * R + 8),
+                "rows_in": m_m * (2 * R + 4),
+                "slots_out": n_m * 12,
+                "bag_fwd": n_m * (R + 4) + nb * (R + 8),
+                "bwd_reduce": n_m * 8 + nb * R + 2 * u_m * R,                  # grad read once per bag (one-hot: per id)
+                "sort_hist": n_m * 4, "sort_scatter": n_m * 16,
+            }
+            if w.multi_hot:
+                model["bwd_reduce"] = n_m * 8 + n_m * R + 2 * u_m * R        # every lookup reads its bag's gradient row
+            ks = {}
+            for name, r in rep.items():
+                avg_us = r["ms"] / r["launches"] * 1e3
+                launches_per_step = r["launches"] / P
+                k = {"avg_us": round(avg_us, 2), "launches_per_step": round(launches_per_step, 2),
+                     "us_per_step": round(avg_us * launches_per_step, 2)}
+                if name in model:
+                    per_launch = model[name] / max(launches_per_step, 1e-9)
+                    k["alg_bytes_per_launch"] = int(per_launch)
+                    k["alg_GBps"] = round(per_launch / (avg_us * 1e-6) / 1e9, 1)
+                ks[name] = k
+            return ks, m_m, e_m
+
+        kernels, m_m, e_m = profile_pass(step, total_steps)
         # HBM-bound kernels on the caller's stream (the sort runs on the auxiliary stream under the miss fill, where
         # its event-bracketed time says more about the fill than about the sort)
         hbm_kernels = [k for k in ("bag_fwd", "bwd_reduce", "evict_gather", "remap_mark", "rank_emit", "rank_count",
@@ -276,7 +285,19 @@ def main():
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(ach / HBM_PEAK_GBS, 4),
                     "traffic": PMC_TRAFFIC_C2.get(dom) if (w.name == "c2" and args.scale == 1.0 and args.cache_ratio == 0.015) else None,
-                    "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"]}
+                    "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"],
+                    "measured": "HIP events around every launch, in the timed schedule (%s)" % args.schedule}
+        if pipelined:
+            # In the pipelined schedule this kernel shares compute units with the host-link row fetch of the next batch
+            # (its waves wait on host reads); the same kernel with the GPU to itself, from a pass in the plain schedule:
+            alone, _, _ = profile_pass(step_plain, total_steps + P)
+            if dom in alone and "alg_GBps" in alone[dom]:
+                roofline["alone"] = {"avg_us": alone[dom]["avg_us"], "achieved": alone[dom]["alg_GBps"],
+                                     "frac": round(alone[dom]["alg_GBps"] / HBM_PEAK_GBS, 4),
+                                     "measured": "HIP events, plain schedule (no other kernel running beside it)"}
+            for name, k in alone.items():
+                if name in kernels:
+                    kernels[name]["alone_avg_us"] = k["avg_us"]
         link = {}
         for name, direction, rows in (("miss_fill", "h2d", m_m), ("evict_store", "d2h", e_m),
                                       ("h2d_block", "h2d", m_m), ("d2h_block", "d2h", e_m)):
@@ -309,7 +330,7 @@ def main():
             orc.embedding_bag_fwd(so, offsets)
             orc.embedding_bag_bwd_sgd(so, offsets, gpool[t % len(gpool)], w.lr)
             t_cpu += time.perf_counter() - a
-            same &= args.lookahead or orc.stats() == stats[t]
+            same &= lookahead or orc.stats() == stats[t]
         cpu_baseline = {"value": round(sum(len(b[0]) for b in batches) / t_cpu, 1), "unit": "ids/s", "cores": 1,
                         "kind": "oracle", "sample": f"first {S} batches of the same trace (prepare+fwd+bwd, warm start)",
                         "host_cores_available": os.cpu_count(), "gpu_stats_identical_on_sample": bool(same)}
@@ -324,9 +345,9 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_features} features in one {w.num_rows} x {w.dim} fp32 table, "
                                f"batch {w.samples} x {w.num_features} {'multi-hot' if w.multi_hot else 'one-hot'} ids, "
                                f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
-                   "schedule": "cache_plan_next(t+1) beside the arrival of batch t's rows | fwd(t), bwd(t) | cache_advance" if pipelined else
-                               ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if args.lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
-                   "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if args.lookahead else "Algorithm 1 as printed",
+                   "schedule": "fwd(t), bwd(t) | cache_plan_next(t+1): index + early row fetch on library streams | cache_advance" if pipelined else
+                               ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
+                   "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if lookahead else "Algorithm 1 as printed",
                    "transmitter": {"dma": "kernel miss fill + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),
                                    "direct": "kernels both ways", "staged": "block transmitter both ways"}[args.transmitter],
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),

@@ -149,9 +149,12 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
  * enqueued on the caller's stream before that call, or finished altogether) and stay untouched until cache_advance;
  * slots_dev must not be the buffer the current batch's forward / backward read.  cache_copy_rows / cache_host_weight
  * reflect the planned batch only after cache_advance.
- * Usage:  cache_prepare(batch 0);  loop { cache_plan_next(batch t+1, slots_next); fwd(t); bwd(t); cache_advance(); }
- * (the call waits on the host for its planning kernels, which run while the rows of batch t are still arriving;
- * calling it after fwd / bwd is equally correct.) */
+ * Usage:  cache_prepare(batch 0);  loop { fwd(t); bwd(t); cache_plan_next(batch t+1, slots_next); cache_advance(); }
+ * (forward / backward are asynchronous and best enqueued first, since this call waits on the host for its planning
+ * kernels; those do not wait for them.  Calling it before them is equally correct.)
+ * The call also starts fetching the planned batch's missing rows, on another library-owned stream, into a block in
+ * device memory (allocated on first use, staging_rows rows per list set); cache_advance then writes the evicted
+ * rows out and copies the fetched rows into their slots. */
 int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                     int32_t* slots_dev);
 /* Makes the batch of the latest cache_prepare_next / cache_plan_next the current one (for cache_plan_next this is

@@ -65,7 +65,7 @@ __global__ void k_set_ctl(Ctl* ctl, int nfree) {
 
 static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
-    for (hipStream_t x : {c->pre, c->pf, c->aux, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
+    for (hipStream_t x : {c->pre, c->pf, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
     c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr; c->pf_dep = nullptr;
     for (PresortRec& r : c->rec) r.valid = false;
@@ -117,7 +117,6 @@ static void destroy(fc_cache* c) {
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : {c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
-    if (c->aux) (void)hipStreamDestroy(c->aux);
     if (c->pre) (void)hipStreamDestroy(c->pre);
     if (c->pf) (void)hipStreamDestroy(c->pf);
     delete c;
@@ -199,9 +198,9 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
         }
     }
     FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-    FC_HIP(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
     FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
     FC_HIP(hipStreamCreateWithFlags(&c->pf, hipStreamNonBlocking));
+    c->aux = c->pf;
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
     for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
@@ -219,6 +218,22 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
 }  // namespace fc
 
 using namespace fc;
+
+// cache_plan_next: the planned batch's missing rows into the arrival block of its list set, on the stream pf
+static int fetch_early(fc_cache* c, int64_t M) {
+    const int k = c->lset;
+    if (!c->arrive[k] && hipMalloc((void**)&c->arrive[k], (size_t)c->staging_rows * c->D * 4) != hipSuccess) {
+        (void)hipGetLastError(); c->arrive[k] = nullptr;
+        return FC_OK;                  // no room for the block: the rows are fetched at cache_advance instead
+    }
+    FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
+    if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
+    if (c->dma_evict) FC_TRY(launch_fill_rows(c, c->pf, M, c->arrive[k], c->staging_rows, c->fill_blocks_early));
+    else FC_TRY(launch_copy_rows(c, c->pf, P_MISS_FILL, c->arrive[k], nullptr, c->staging_rows, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
+    FC_HIP(hipEventRecord(c->ev_arrive[k], c->pf));
+    c->planned.arrived = true;
+    return FC_OK;
+}
 
 // the caller's stream takes over from the look-ahead stream: everything cache_prepare_next enqueued comes first
 static int adopt_next(fc_cache* c) {
@@ -320,29 +335,22 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     MovePlan mv;
     const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv);
     c->pst = c->stream;
-    FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
     c->last_pst = c->pre;
     c->next_pending = true;
-    if (rc != FC_OK) return rc;
+    if (rc != FC_OK) {
+        FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
+        return rc;
+    }
+    c->planned = mv;
+    int rc2 = FC_OK;
     // Missing rows ahead of time: they are not resident, so nothing the caller's stream still does to the current
     // batch changes them; their newest copy is in the host table or in an evicted-row block (transit marks), and the
     // latest row movement, which produced both, is the only thing to wait for.  Victims leave, and these rows enter
     // their slots, at cache_advance.
-    c->planned = mv;
-    if (mv.M > 0 && mv.M <= c->staging_rows) {
-        const int k = c->lset;
-        if (!c->arrive[k] && hipMalloc((void**)&c->arrive[k], (size_t)c->staging_rows * c->D * 4) != hipSuccess) {
-            (void)hipGetLastError(); c->arrive[k] = nullptr;
-            return FC_OK;                  // no room for the block: the rows are fetched at cache_advance instead
-        }
-        FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
-        if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
-        if (c->dma_evict) FC_TRY(launch_fill_rows(c, c->pf, mv.M, c->arrive[k], c->staging_rows, c->fill_blocks_early));
-        else FC_TRY(launch_copy_rows(c, c->pf, P_MISS_FILL, c->arrive[k], nullptr, c->staging_rows, c->host_dev, c->miss_ranks, c->N, mv.M, c->fill_blocks));
-        FC_HIP(hipEventRecord(c->ev_arrive[k], c->pf));
-        c->planned.arrived = true;
-    }
-    return FC_OK;
+    if (mv.M > 0 && mv.M <= c->staging_rows) rc2 = fetch_early(c, mv.M);
+    if (n > 0) { c->pst = c->pre; (void)presort_impl(c, slots_dev, n, offsets_dev, num_bags); c->pst = c->stream; }
+    FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
+    return rc2;
 }
 
 int cache_advance(fc_cache* c) {

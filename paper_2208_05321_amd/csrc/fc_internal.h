@@ -109,7 +109,7 @@ struct fc_cache {
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
                                     // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through
-    int fill_blocks_early = 60;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
+    int fill_blocks_early = 48;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
     int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
     int evict_early = 2;            // when that kernel starts (tuning: FC_EVICT_EARLY): 0 after the miss fill, under
                                     // forward/backward; 1 right after the gather; 2 together with the miss fill
@@ -172,7 +172,8 @@ struct fc_cache {
 
     // sort of the (slot, bag) pairs started by cache_prepare on the auxiliary stream
     bool presort = true;            // FC_NO_PRESORT clears it
-    hipStream_t aux = nullptr;
+    hipStream_t aux = nullptr;      // = pf, or pre when cache_plan_next indexes there (pf then fetches rows): the device
+                                    // offers four hardware queues, so the library keeps to three streams of its own
     hipEvent_t ev_slots = nullptr;
     fc::PresortRec rec[2];
     int rec_next = 0;

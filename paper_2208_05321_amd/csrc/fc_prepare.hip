@@ -596,26 +596,17 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
             k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
                                                       c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
-        // every row of the batch has its slot now: write the slots out and start sorting them for the backward
-        // pass on the auxiliary stream (it will run while the missing rows cross the host link)
-        if (n > 0) {
-            {
-                ProfScope ps(c, P_SLOTS_OUT, st);
-                k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
-            }
-            (void)presort_impl(c, slots, n, offsets, num_bags);   // on failure the backward pass sorts (and reports) itself
-        }
     }
-    if (M == 0 && n > 0) {
-        {
-            ProfScope ps(c, P_SLOTS_OUT, st);
-            k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
-        }
-        (void)presort_impl(c, slots, n, offsets, num_bags);
+    // every row of the batch has its slot now: write the slots out (the caller then starts sorting them for the
+    // backward pass on the auxiliary stream, where the sort runs while the missing rows cross the host link)
+    if (n > 0) {
+        ProfScope ps(c, P_SLOTS_OUT, st);
+        k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
     }
     FC_HIP(hipGetLastError());
     FC_HIP(hipEventRecord(c->ev_index_done, st));
     c->last_index_stream = st;
+    c->aux = (st == c->pre && !lookahead) ? c->pre : c->pf;
     mv->valid = true; mv->M = M; mv->need = need; mv->buf = buf;
     c->last.n_ids = n;
     c->last.n_unique = h.n_unique;
@@ -687,6 +678,7 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
     FC_TRY(prepare_index(c, st, lookahead, ids, n, offsets, num_bags, slots, &mv));
     // Look-ahead: rows about to be evicted or overwritten may still be in use by work the caller enqueued before
     // this call (the backward pass of the batch before the current one); the index decisions did not care.
+    if (n > 0) (void)presort_impl(c, slots, n, offsets, num_bags);   // on failure the backward pass sorts (and reports) itself
     if (lookahead) FC_HIP(hipStreamWaitEvent(st, c->ev_s_now, 0));
     return prepare_move(c, st, mv);
 }

@@ -326,43 +326,64 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
 //     a) empty slots per tile of FREE_TILE slots;  b) each tile ranks its empty slots after the tiles below it.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int FREE_TILE = 1024;
+// 256 threads with 4 consecutive slots each: a workgroup this small finds room on a compute unit at once, also while
+// the forward / backward kernels of the previous batch fill the chip (cache_plan_next)
+constexpr int FREE_THREADS = 256;
+constexpr int FREE_PER = FREE_TILE / FREE_THREADS;
 
-__global__ __launch_bounds__(FREE_TILE) void k_free_count(const int32_t* __restrict__ slot_rank, int C,
-                                                          int32_t* __restrict__ tcount) {
-    __shared__ int red[FREE_TILE / 64];
-    const int s = blockIdx.x * FREE_TILE + threadIdx.x;
-    const bool empty = s < C && slot_rank[s] == -1;
-    const uint64_t b = __ballot(empty);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = __popcll(b);
+// bit k set: slot s0 + k is empty
+__device__ __forceinline__ unsigned empty_mask(const int32_t* __restrict__ slot_rank, int s0, int C) {
+    unsigned m = 0;
+    if (s0 + FREE_PER <= C) {
+        const int4 v = *reinterpret_cast<const int4*>(slot_rank + s0);
+        m = (v.x == -1 ? 1u : 0u) | (v.y == -1 ? 2u : 0u) | (v.z == -1 ? 4u : 0u) | (v.w == -1 ? 8u : 0u);
+    } else {
+        for (int k = 0; k < FREE_PER; ++k) if (s0 + k < C && slot_rank[s0 + k] == -1) m |= 1u << k;
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(FREE_THREADS) void k_free_count(const int32_t* __restrict__ slot_rank, int C,
+                                                             int32_t* __restrict__ tcount) {
+    static_assert(FREE_PER == 4, "empty_mask reads four slots at a time");
+    __shared__ int red[FREE_THREADS / 64];
+    const int s0 = blockIdx.x * FREE_TILE + threadIdx.x * FREE_PER;
+    const int e = __popc(empty_mask(slot_rank, s0, C));
+    const int w = wave_sum(e);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
     __syncthreads();
     if (threadIdx.x == 0) {
         int t = 0;
 #pragma unroll
-        for (int k = 0; k < FREE_TILE / 64; ++k) t += red[k];
+        for (int k = 0; k < FREE_THREADS / 64; ++k) t += red[k];
         tcount[blockIdx.x] = t;
     }
 }
 
-__global__ __launch_bounds__(FREE_TILE) void k_free_assign(int32_t* slot_rank, int C, const int32_t* __restrict__ tcount,
-                                                           int M, const int32_t* __restrict__ miss_ranks,
-                                                           int32_t* __restrict__ fill_slots, int32_t* rank_slot,
-                                                           int32_t* __restrict__ fill_src) {
-    __shared__ int lds[FREE_TILE / 64];
+__global__ __launch_bounds__(FREE_THREADS) void k_free_assign(int32_t* slot_rank, int C, const int32_t* __restrict__ tcount,
+                                                              int M, const int32_t* __restrict__ miss_ranks,
+                                                              int32_t* __restrict__ fill_slots, int32_t* rank_slot,
+                                                              int32_t* __restrict__ fill_src) {
+    __shared__ int lds[FREE_THREADS / 64];
     int part = 0;
-    for (int g = threadIdx.x; g < (int)blockIdx.x; g += FREE_TILE) part += tcount[g];
+    for (int g = threadIdx.x; g < (int)blockIdx.x; g += FREE_THREADS) part += tcount[g];
     int base;
-    (void)block_excl_scan<FREE_TILE>(part, base, lds);
+    (void)block_excl_scan<FREE_THREADS>(part, base, lds);
     if (base >= M) return;                                   // all missing rows were placed in lower tiles
-    const int s = blockIdx.x * FREE_TILE + threadIdx.x;
-    const bool empty = s < C && slot_rank[s] == -1;
+    const int s0 = blockIdx.x * FREE_TILE + threadIdx.x * FREE_PER;
+    const unsigned m = empty_mask(slot_rank, s0, C);
     int tot;
-    const int j = base + block_excl_scan<FREE_TILE>(empty ? 1 : 0, tot, lds);
-    if (empty && j < M) {
+    int j = base + block_excl_scan<FREE_THREADS>(__popc(m), tot, lds);
+    for (int k = 0; k < FREE_PER; ++k) {
+        if (!((m >> k) & 1u)) continue;
+        if (j >= M) break;
+        const int s = s0 + k;
         const int r = miss_ranks[j];
         fill_slots[j] = s;
         slot_rank[s] = r;
         if (fill_src) fill_src[j] = rank_slot[r];     // -1: host table; <= -2: evicted-row block (in transit)
         rank_slot[r] = s;
+        ++j;
     }
 }
 
@@ -590,10 +611,10 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
             const unsigned tiles = (unsigned)cdiv(c->C, FREE_TILE);
             {
                 ProfScope ps(c, P_FREE_COUNT, st);
-                k_free_count<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount);
+                k_free_count<<<tiles, FREE_THREADS, 0, st>>>(c->slot_rank, (int)c->C, c->tcount);
             }
             ProfScope ps(c, P_FREE_PICK, st);
-            k_free_assign<<<tiles, FREE_TILE, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
+            k_free_assign<<<tiles, FREE_THREADS, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
                                                       c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
     }

@@ -28,7 +28,11 @@
  *   - "cache_capacity" in evict_num = numel(miss) - cache_capacity is the number
  *     of currently empty slots (otherwise nothing would ever be evicted).
  *   - evicted rows are always written back (the paper tracks no dirty state),
- *     after which both map entries are reset to -1.
+ *     after which both map entries are reset to -1.  Optional variant, not in
+ *     the paper (fco_set_dirty_tracking): a resident row is dirty once a
+ *     backward pass has updated it since it was loaded; only dirty victims
+ *     are written back (a clean row equals its copy in the CPU Weight), and
+ *     bytes_d2h counts those alone.  Values never differ between the two.
  *   - the j-th smallest missing cpu_row_idx goes to the j-th smallest empty
  *     slot (unique() returns ascending values, nonzero() ascending indices).
  *   - victims: the evict_num resident rows with the largest cpu_row_idx among
@@ -70,6 +74,9 @@ typedef struct fco {
     /* look-ahead variant: rows of the previously prepared batch (ascending), also protected from eviction */
     int32_t* prev_U;       /* [C]                                          */
     int64_t n_prev;
+    /* dirty-tracking variant: dirty[s] = 1 once slot s was updated after it was loaded */
+    int32_t dirty_track;
+    unsigned char* dirty;  /* [C]                                          */
 } fco;
 
 static int cmp_i32(const void* a, const void* b) {
@@ -93,7 +100,7 @@ static int contains_sorted(const int32_t* a, int64_t n, int32_t v) {
 void fco_destroy(fco* o) {
     if (!o) return;
     free(o->rank); free(o->cache); free(o->slot_rank); free(o->rank_slot);
-    free(o->miss_ranks); free(o->evict_ranks); free(o->evict_slots); free(o->fill_slots); free(o->prev_U);
+    free(o->miss_ranks); free(o->evict_ranks); free(o->evict_slots); free(o->fill_slots); free(o->prev_U); free(o->dirty);
     free(o);
 }
 
@@ -122,7 +129,8 @@ int fco_create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float*
     o->fill_slots = (int32_t*)malloc((size_t)C * 4);
     o->prev_U = (int32_t*)malloc((size_t)C * 4);
     o->n_prev = 0;
-    if (!o->prev_U ||  !o->rank || !o->cache || !o->slot_rank || !o->rank_slot || !o->miss_ranks || !o->evict_ranks ||
+    o->dirty = (unsigned char*)calloc((size_t)C, 1);
+    if (!o->prev_U || !o->dirty ||  !o->rank || !o->cache || !o->slot_rank || !o->rank_slot || !o->miss_ranks || !o->evict_ranks ||
         !o->evict_slots || !o->fill_slots) { fco_destroy(o); return FCO_OOM; }
     memcpy(o->rank, freq_rank, (size_t)N * 4);
     for (int64_t r = 0; r < N; ++r) o->rank_slot[r] = -1;
@@ -177,7 +185,7 @@ static int prepare_core(fco* o, const int64_t* ids, int64_t n, const int64_t* of
     int64_t empty = 0;
     for (int64_t s = 0; s < C; ++s) if (o->slot_rank[s] == -1) ++empty;
     int64_t evict_num = nM - empty;
-    int64_t nV = 0;
+    int64_t nV = 0, n_written = 0;
     if (evict_num > 0) {
         /* rows of the current batch (the "backlist") are protected; among the other resident rows
            take the evict_num largest cpu_row_idx (LFU by static frequency rank, Section 4.3) */
@@ -203,7 +211,11 @@ static int prepare_core(fco* o, const int64_t* ids, int64_t n, const int64_t* of
         /* data_transmitter.move_to_cpu, then the slots become empty */
         for (int64_t j = 0; j < nV; ++j) {
             int32_t s = o->evict_slots[j], k = o->evict_ranks[j];
-            memcpy(o->host + (size_t)k * D, o->cache + (size_t)s * D, (size_t)D * 4);
+            if (!o->dirty_track || o->dirty[s]) {
+                memcpy(o->host + (size_t)k * D, o->cache + (size_t)s * D, (size_t)D * 4);
+                ++n_written;
+            }
+            o->dirty[s] = 0;                   /* the slot is empty; whatever is loaded next equals its CPU copy */
             o->rank_slot[k] = -1;
             o->slot_rank[s] = -1;
         }
@@ -225,7 +237,7 @@ static int prepare_core(fco* o, const int64_t* ids, int64_t n, const int64_t* of
 
     o->n_ids = n; o->n_unique = nU; o->n_hit_unique = nH; o->n_hit_ids = hit_ids;
     o->n_miss = nM; o->n_evict = nV;
-    o->bytes_h2d = nM * (int64_t)D * 4; o->bytes_d2h = nV * (int64_t)D * 4;
+    o->bytes_h2d = nM * (int64_t)D * 4; o->bytes_d2h = n_written * (int64_t)D * 4;
     memcpy(o->prev_U, U, (size_t)nU * 4);     /* this batch is the "previous" one of the next call */
     o->n_prev = nU;
     free(r); free(U);
@@ -282,6 +294,7 @@ int fco_embedding_bag_bwd_sgd(fco* o, const int32_t* slots, int64_t n, const int
             float step = lr * gs[c];            /* rounded product (no contraction), then the subtraction */
             row[c] = row[c] - step;
         }
+        o->dirty[s] = 1;
     }
     free(g); free(touched);
     return FCO_OK;
@@ -292,10 +305,20 @@ int fco_flush(fco* o) {
     if (!o) return FCO_INVALID_ARG;
     for (int64_t s = 0; s < o->C; ++s) {
         int32_t k = o->slot_rank[s];
-        if (k >= 0) memcpy(o->host + (size_t)k * o->D, o->cache + (size_t)s * o->D, (size_t)o->D * 4);
+        if (k >= 0 && (!o->dirty_track || o->dirty[s]))
+            memcpy(o->host + (size_t)k * o->D, o->cache + (size_t)s * o->D, (size_t)o->D * 4);
+        o->dirty[s] = 0;                       /* the CPU Weight is current for every resident row now */
     }
     return FCO_OK;
 }
+
+/* Variant beyond the paper: write back only victims that a backward pass has updated since they were loaded. */
+int fco_set_dirty_tracking(fco* o, int32_t on) {
+    if (!o) return FCO_INVALID_ARG;
+    o->dirty_track = on ? 1 : 0;
+    return FCO_OK;
+}
+const unsigned char* fco_dirty(const fco* o) { return o->dirty; }
 
 /* ---- accessors for the tests ---- */
 void fco_stats(const fco* o, int64_t out[8]) {

@@ -55,8 +55,10 @@ def _load(path: str | None = None):
         L.fco_destroy.restype = None
         L.fco_stats.argtypes = [vp, vp]
         L.fco_stats.restype = None
+        L.fco_set_dirty_tracking.argtypes = [vp, i32]
+        L.fco_set_dirty_tracking.restype = ctypes.c_int
         for name in ("fco_slot_rank", "fco_rank_slot", "fco_cache", "fco_miss_ranks", "fco_evict_ranks",
-                     "fco_evict_slots", "fco_fill_slots"):
+                     "fco_evict_slots", "fco_fill_slots", "fco_dirty"):
             getattr(L, name).argtypes = [vp]
             getattr(L, name).restype = vp
         if path is not None:
@@ -72,7 +74,8 @@ class Oracle:
     """Owns the oracle's cached weight and maps; `host` (fp32 [N, D], rank-ordered) is the caller's array
     and is updated in place by evictions and flush."""
 
-    def __init__(self, freq_rank: np.ndarray, host: np.ndarray, cache_rows: int, warm: bool = True, lib=None):
+    def __init__(self, freq_rank: np.ndarray, host: np.ndarray, cache_rows: int, warm: bool = True, lib=None,
+                 dirty_tracking: bool = False):
         L = lib if lib is not None else _load()
         self._L = L
         self.freq_rank = np.ascontiguousarray(freq_rank, dtype=np.int32)
@@ -88,6 +91,8 @@ class Oracle:
         if rc:
             raise OracleError(rc)
         self._h = h
+        if dirty_tracking:          # variant beyond the paper: only victims updated since they were loaded are written back
+            L.fco_set_dirty_tracking(h, 1)
 
     def close(self):
         if getattr(self, "_h", None):
@@ -157,6 +162,10 @@ class Oracle:
     @property
     def cache(self):
         return self._view("fco_cache", self.C * self.D, np.float32).reshape(self.C, self.D)
+
+    @property
+    def dirty(self):
+        return self._view("fco_dirty", self.C, np.uint8)
 
     def last_lists(self) -> dict:
         s = self.stats()

@@ -12,6 +12,7 @@ import pytest
 
 from oracle.wrapper import Oracle, OracleError, _load, _SRC
 from tests.alg1_arrayops import ArrayOpsCache
+from tests.test_oracle_dirty import DIRTY_PINS
 from workloads import table_values
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -24,6 +25,9 @@ def offs(n):
 def battery(lib):
     """Raises AssertionError (or OracleError) if the oracle build `lib` violates a pin."""
     mk = lambda fr, host, C, warm: Oracle(fr, host, C, warm=warm, lib=lib)
+    # the dirty-tracking variant (values unchanged, write-back set against an independent model, hand-worked bytes)
+    for pin in DIRTY_PINS:
+        pin(lambda fr, host, C, warm, dirty: Oracle(fr, host, C, warm=warm, lib=lib, dirty_tracking=dirty))
     # P0 hand-worked traces
     g = json.load(open(os.path.join(HERE, "golden", "alg1_handworked.json")))
     fr = np.array(g["freq_rank"], dtype=np.int32)
@@ -122,8 +126,8 @@ MUTANTS = [
     ("look-ahead protection ignored", "if (protect_prev && contains_sorted(o->prev_U, o->n_prev, k)) continue;", ""),
     ("evicts one row too many", "int64_t evict_num = nM - empty;", "int64_t evict_num = nM - empty + 1;"),
     ("evicts against total capacity", "int64_t evict_num = nM - empty;", "int64_t evict_num = nM - C;"),
-    ("no write-back", "memcpy(o->host + (size_t)k * D, o->cache + (size_t)s * D, (size_t)D * 4);\n            o->rank_slot[k] = -1;",
-     "o->rank_slot[k] = -1;"),
+    ("no write-back", "memcpy(o->host + (size_t)k * D, o->cache + (size_t)s * D, (size_t)D * 4);\n                ++n_written;",
+     "++n_written;"),
     ("inverse map not reset on eviction", "            o->rank_slot[k] = -1;\n            o->slot_rank[s] = -1;", "            o->slot_rank[s] = -1;"),
     ("misses take the highest empty slots", "for (int64_t s = 0; s < C && j < nM; ++s) {", "for (int64_t s = C - 1; s >= 0 && j < nM; --s) {"),
     ("missed row not loaded", "memcpy(o->cache + (size_t)s * D, o->host + (size_t)k * D, (size_t)D * 4);\n            o->slot_rank[s] = k;",
@@ -135,10 +139,16 @@ MUTANTS = [
     ("gradient of the wrong bag", "const float* gb = grad_out + (size_t)b * D;", "const float* gb = grad_out + (size_t)(b > 0 ? b - 1 : 0) * D;"),
     ("warm-up in reverse order", "o->slot_rank[s] = (int32_t)s;\n            o->rank_slot[s] = (int32_t)s;\n            memcpy(o->cache + (size_t)s * D, host + (size_t)s * D, (size_t)D * 4);",
      "o->slot_rank[s] = (int32_t)(C - 1 - s);\n            o->rank_slot[C - 1 - s] = (int32_t)s;\n            memcpy(o->cache + (size_t)s * D, host + (size_t)(C - 1 - s) * D, (size_t)D * 4);"),
-    ("flush skips a slot", "for (int64_t s = 0; s < o->C; ++s) {\n        int32_t k = o->slot_rank[s];\n        if (k >= 0) memcpy(o->host",
-     "for (int64_t s = 1; s < o->C; ++s) {\n        int32_t k = o->slot_rank[s];\n        if (k >= 0) memcpy(o->host"),
+    ("flush skips a slot", "for (int64_t s = 0; s < o->C; ++s) {\n        int32_t k = o->slot_rank[s];\n        if (k >= 0 &&",
+     "for (int64_t s = 1; s < o->C; ++s) {\n        int32_t k = o->slot_rank[s];\n        if (k >= 0 &&"),
     ("bytes counted per float", "o->bytes_h2d = nM * (int64_t)D * 4;", "o->bytes_h2d = nM * (int64_t)D;"),
     ("duplicate ids counted as distinct rows", "if (i == 0 || U[i] != U[i - 1]) U[nU++] = U[i];", "U[nU++] = U[i];"),
+    ("dirty tracking: backward does not mark rows", "        o->dirty[s] = 1;\n", ""),
+    ("dirty tracking: an evicted slot stays dirty", "            o->dirty[s] = 0;                   /* the slot is empty; whatever is loaded next equals its CPU copy */\n", ""),
+    ("dirty tracking: clean rows written, dirty rows dropped", "if (!o->dirty_track || o->dirty[s]) {", "if (!o->dirty_track || !o->dirty[s]) {"),
+    ("dirty tracking: bytes still count every victim", "o->bytes_d2h = n_written * (int64_t)D * 4;", "o->bytes_d2h = nV * (int64_t)D * 4;"),
+    ("dirty tracking: flush leaves rows dirty", "        o->dirty[s] = 0;                       /* the CPU Weight is current for every resident row now */\n", ""),
+    ("dirty tracking: flush writes clean rows only", "if (k >= 0 && (!o->dirty_track || o->dirty[s]))", "if (k >= 0 && (!o->dirty_track || !o->dirty[s]))"),
     ("rank lookup skipped", "for (int64_t i = 0; i < n; ++i) r[i] = o->rank[ids[i]];", "for (int64_t i = 0; i < n; ++i) r[i] = (int32_t)ids[i];"),
 ]
 

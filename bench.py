@@ -90,6 +90,11 @@ def main():
                          "plain: cache_prepare(t), fwd(t), bwd(t), everything on one stream; "
                          "lookahead: cache_prepare_next(t+1) before fwd(t), bwd(t) - a different cache policy (the previous "
                          "batch's rows are protected too), not the headline configuration")
+    ap.add_argument("--dirty-tracking", action="store_true",
+                    help="FC_DIRTY_TRACK: only victims updated since they were loaded are written back (a variant beyond the "
+                         "paper; plain schedule only)")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="no backward pass (inference): a different metric, ids/s through cache prepare + EmbeddingBag forward")
     ap.add_argument("--static-module", action="store_true",
                     help="instead of the per-batch path, time the GPU build of the static module (id counting + ranking)")
     ap.add_argument("--staging-rows", type=int, default=0)
@@ -123,7 +128,7 @@ def main():
 
     cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
                       warm=False, staged=args.transmitter == "staged", stream=stream,
-                      dma_evict=args.transmitter == "dma")
+                      dma_evict=args.transmitter == "dma", dirty_tracking=args.dirty_tracking, presort=not args.forward_only)
     host = cache.host_weight()
     w.host_table(out=host)
     cache.warm()
@@ -160,7 +165,8 @@ def main():
         cache.prepare(ids_d[t], off_d[t], out=s)
         stats.append(cache.stats())
         cache.embedding_bag_fwd(s, off_d[t], out=out)
-        cache.embedding_bag_bwd_sgd(s, off_d[t], grads[t % len(grads)], w.lr)
+        if not args.forward_only:
+            cache.embedding_bag_bwd_sgd(s, off_d[t], grads[t % len(grads)], w.lr)
 
     def step_lookahead(t):
         # batch t was prepared by the previous step (or just below for the very first one)
@@ -200,8 +206,8 @@ def main():
         stats.append(cache.stats())
         cache.advance()
 
-    if args.schedule == "pipelined" and args.transmitter == "staged":
-        args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter
+    if args.schedule == "pipelined" and (args.transmitter == "staged" or args.dirty_tracking or args.forward_only):
+        args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter or dirty tracking
     pipelined, lookahead = args.schedule == "pipelined", args.schedule == "lookahead"
     step = step_lookahead if lookahead else (step_planned if pipelined else step_plain)
 
@@ -318,7 +324,7 @@ def main():
         S = min(args.cpu_batches, total_steps)
         host_o = np.empty_like(host)
         w.host_table(out=host_o)
-        orc = Oracle(w.freq_rank, host_o, w.cache_rows, warm=True)
+        orc = Oracle(w.freq_rank, host_o, w.cache_rows, warm=True, dirty_tracking=args.dirty_tracking)
         batches = [w.batch(t) for t in range(S)]
         gpool = [w.grad(k, nb).copy() for k in range(w.grad_pool)]
         t_cpu = 0.0
@@ -328,7 +334,8 @@ def main():
             a = time.perf_counter()
             so = orc.prepare(ids, offsets)
             orc.embedding_bag_fwd(so, offsets)
-            orc.embedding_bag_bwd_sgd(so, offsets, gpool[t % len(gpool)], w.lr)
+            if not args.forward_only:
+                orc.embedding_bag_bwd_sgd(so, offsets, gpool[t % len(gpool)], w.lr)
             t_cpu += time.perf_counter() - a
             same &= lookahead or orc.stats() == stats[t]
         cpu_baseline = {"value": round(sum(len(b[0]) for b in batches) / t_cpu, 1), "unit": "ids/s", "cores": 1,
@@ -338,7 +345,8 @@ def main():
         orc.close()
 
     result = {
-        "metric": "ids/sec through cache prepare + EmbeddingBag fwd/bwd at 1.5% cache",
+        "metric": "ids/sec through cache prepare + EmbeddingBag fwd/bwd at 1.5% cache" if not args.forward_only else
+                  "ids/sec through cache prepare + EmbeddingBag fwd (no backward pass) at 1.5% cache",
         "value": round(value, 1), "unit": "ids/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
@@ -347,7 +355,8 @@ def main():
                                f"Zipf({w.alpha}), cache {w.cache_rows} rows ({args.cache_ratio:.3%}), SGD lr {w.lr}",
                    "schedule": "fwd(t), bwd(t) | cache_plan_next(t+1): index + early row fetch on library streams | cache_advance" if pipelined else
                                ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
-                   "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if lookahead else "Algorithm 1 as printed",
+                   "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if lookahead else
+                             ("Algorithm 1, clean victims not written back" if args.dirty_tracking else "Algorithm 1 as printed"),
                    "transmitter": {"dma": "kernel miss fill + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),
                                    "direct": "kernels both ways", "staged": "block transmitter both ways"}[args.transmitter],
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),

@@ -40,9 +40,9 @@ typedef struct fc_stats {
     int64_t n_hit_unique; /* of those, already resident                                  */
     int64_t n_hit_ids;    /* ids whose row was already resident (access-level hits)      */
     int64_t n_miss;       /* rows moved host -> HBM                                      */
-    int64_t n_evict;      /* rows moved HBM -> host                                      */
+    int64_t n_evict;      /* rows evicted (all written to the host table unless FC_DIRTY_TRACK) */
     int64_t bytes_h2d;    /* n_miss  * dim * 4                                           */
-    int64_t bytes_d2h;    /* n_evict * dim * 4                                           */
+    int64_t bytes_d2h;    /* n_evict * dim * 4 (FC_DIRTY_TRACK: dirty victims * dim * 4)  */
 } fc_stats;
 
 enum {
@@ -74,10 +74,18 @@ enum {
                                The host table is complete after cache_flush (or cache_check).  Number of threads:
                                environment variable FC_SCATTER_THREADS (default 8).  Not with FC_TRANSMIT_STAGED.
                                Results are identical. */
-    FC_NO_PRESORT = 8       /* By default cache_prepare also starts, on a library-owned stream, the sort of the
+    FC_NO_PRESORT = 8,      /* By default cache_prepare also starts, on a library-owned stream, the sort of the
                                batch's (slot, bag) pairs that embedding_bag_bwd_sgd needs, so that it overlaps the
                                miss fill; it reads slots_dev and offsets_dev until it is done.  Set this flag when
                                no backward pass follows (inference) or those buffers are reused at once. */
+    FC_DIRTY_TRACK = 16     /* Variant beyond the paper (Algorithm 1 always calls move_to_cpu): a resident row is
+                               dirty once embedding_bag_bwd_sgd has updated it since it was loaded; only dirty
+                               victims are written back, clean ones are dropped (their copy in the host table is
+                               current), and cache_flush writes dirty rows only.  bytes_d2h counts the rows written.
+                               Every other result is unchanged.  cache_prepare then waits on the host once more (for
+                               the number of dirty victims); cache_prepare_next / cache_plan_next are not available
+                               with this flag (FC_ERR_INVALID_ARG): what is dirty is only known after the current
+                               batch's backward pass. */
 };
 
 /* Static module + dynamic module set-up (Sections 4.2, 4.3).

@@ -78,6 +78,7 @@ static int reset_state(fc_cache* c, bool warm) {
     k_bits_prefix<<<256, 256, 0, st>>>(c->rbits, words, warm ? c->C : 0);
     k_set_ctl<<<1, 1, 0, st>>>(c->ctl, warm ? 0 : (int)c->C);
     FC_HIP(hipGetLastError());
+    if (c->dirty) FC_HIP(hipMemsetAsync(c->dirty, 0, (size_t)c->C, st));   // loaded rows equal their host copies
     if (warm) FC_HIP(hipMemcpyAsync(c->cache, c->host, (size_t)c->C * c->D * 4, hipMemcpyHostToDevice, st));
     else FC_HIP(hipMemsetAsync(c->cache, 0, (size_t)c->C * c->D * 4, st));   // empty slots read as zeros
     FC_HIP(hipStreamSynchronize(st));
@@ -98,6 +99,9 @@ static void destroy(fc_cache* c) {
         if (c->ev_d2h[b]) (void)hipEventDestroy(c->ev_d2h[b]);
     }
     for (auto& set : c->lists) for (int32_t* p : set) if (p) (void)hipFree(p);
+    if (c->dirty) (void)hipFree(c->dirty);
+    if (c->dcount) (void)hipFree(c->dcount);
+    if (c->dctl) (void)hipHostFree(c->dctl);
     for (int k = 0; k < 2; ++k) {
         if (c->arrive[k]) (void)hipFree(c->arrive[k]);
         if (c->ev_arrive[k]) (void)hipEventDestroy(c->ev_arrive[k]);
@@ -172,9 +176,19 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     FC_HIP(hipMalloc((void**)&c->vtake, (size_t)c->NB * 4));
     FC_HIP(hipMalloc((void**)&c->voff, (size_t)c->NB * 4));
     c->dma_evict = (flags & FC_EVICT_DMA) != 0;
+    c->dirty_track = (flags & FC_DIRTY_TRACK) != 0;
     for (auto& set : c->lists)
-        for (int k = 0; k < 5; ++k)
-            if (k < 3 || (k == 3 ? c->dma_evict : !c->dma_evict)) FC_HIP(hipMalloc((void**)&set[k], (size_t)C * 4));
+        for (int k = 0; k < 7; ++k) {
+            const bool wanted = k < 3 || (k == 3 && c->dma_evict) || (k == 4 && (!c->dma_evict || c->dirty_track)) ||
+                                (k >= 5 && c->dirty_track);
+            if (wanted) FC_HIP(hipMalloc((void**)&set[k], (size_t)C * 4));
+        }
+    if (c->dirty_track) {
+        FC_HIP(hipMalloc((void**)&c->dirty, (size_t)C));
+        FC_HIP(hipMalloc((void**)&c->dcount, (size_t)cdiv(C, 1024) * 4));
+        if (hipHostMalloc((void**)&c->dctl, 2 * sizeof(int32_t), hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return FC_ERR_OOM_PINNED; }
+        c->dctl[0] = c->dctl[1] = 0;
+    }
     if (c->dma_evict) {
         for (int b = 0; b < DMA_BLOCKS; ++b) {
             FC_HIP(hipMalloc((void**)&c->vrank_buf[b], (size_t)C * 4));
@@ -258,7 +272,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
-        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT)) ||
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT | FC_DIRTY_TRACK)) ||
         ((flags & FC_TRANSMIT_STAGED) && (flags & FC_EVICT_DMA)))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
@@ -302,7 +316,7 @@ int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t*
 
 int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                        int32_t* slots_dev) {
-    if (!c) return FC_ERR_INVALID_ARG;
+    if (!c || c->dirty_track) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     // everything the caller has enqueued so far (the backward pass of the batch before the current one, and the
     // input buffers of this call) is complete before this call's row movement, or before all of it when the last
@@ -325,7 +339,7 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
 
 int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                     int32_t* slots_dev) {
-    if (!c || (c->flags & FC_TRANSMIT_STAGED)) return FC_ERR_INVALID_ARG;
+    if (!c || (c->flags & FC_TRANSMIT_STAGED) || c->dirty_track) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     if (c->planned.valid) FC_TRY(cache_advance(c));
     // The index half touches no rows, so it need not wait for the row movement, forward or backward work the caller
@@ -387,6 +401,11 @@ int cache_flush(fc_cache* c) {
         std::vector<int32_t> sr((size_t)c->C);
         FC_HIP(hipMemcpyAsync(sr.data(), c->slot_rank, (size_t)c->C * 4, hipMemcpyDeviceToHost, c->stream));
         FC_HIP(hipStreamSynchronize(c->stream));
+        if (c->dirty) {                // dirty rows only: a clean slot counts as empty for the scatter below
+            std::vector<uint8_t> dr((size_t)c->C);
+            FC_HIP(hipMemcpy(dr.data(), c->dirty, (size_t)c->C, hipMemcpyDeviceToHost));
+            for (int64_t s = 0; s < c->C; ++s) if (!dr[s]) sr[s] = -1;
+        }
         const size_t rowb = (size_t)c->D * 4;
         for (int64_t s0 = 0; s0 < c->C; s0 += c->staging_rows) {
             const int64_t rows = c->C - s0 < c->staging_rows ? c->C - s0 : c->staging_rows;
@@ -399,9 +418,10 @@ int cache_flush(fc_cache* c) {
             for (int64_t j = 0; j < rows; ++j)
                 if (sr[s0 + j] >= 0) memcpy(c->host + (size_t)sr[s0 + j] * c->D, c->stage_pin + (size_t)j * c->D, rowb);
         }
-        return FC_OK;
+    } else {
+        FC_TRY(launch_flush_rows(c, c->stream));
     }
-    FC_TRY(launch_flush_rows(c, c->stream));
+    if (c->dirty) FC_HIP(hipMemsetAsync(c->dirty, 0, (size_t)c->C, c->stream));   // the host table is current for every resident row
     FC_HIP(hipStreamSynchronize(c->stream));
     return FC_OK;
 }

@@ -216,6 +216,15 @@ __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ 
     if (threadIdx.x == 0) bmeta[blockIdx.x] = blockmeta;
 }
 
+// FC_DIRTY_TRACK: every slot the backward pass updates differs from its host copy from now on.
+__global__ __launch_bounds__(256) void k_mark_dirty(const int32_t* __restrict__ slots, int n, int C, uint8_t* __restrict__ dirty) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const int s = slots[i];
+        if ((unsigned)s < (unsigned)C) dirty[s] = 1;
+    }
+}
+
 // Runs that cross workgroup borders: the workgroup where the run starts adds the later workgroups' pieces in order.
 template <int VEC>
 __global__ __launch_bounds__(256) void k_bwd_fixup(int C, float* cache, int D, int lpr_shift, float lr,
@@ -347,6 +356,7 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
         FC_TRY(sort_pairs(c, c->sb[2], st, slots, n, offsets, num_bags, &kin, &vin));
     }
     const int sh = shift_of(c->lpr);
+    if (c->dirty) k_mark_dirty<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(slots, (int)n, (int)c->C, c->dirty);
     {
         ProfScope ps(c, P_BWD_REDUCE, st);
         BwdMeta* bm = reinterpret_cast<BwdMeta*>(c->pmeta);

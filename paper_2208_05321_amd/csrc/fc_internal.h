@@ -66,7 +66,7 @@ struct SortBufs {
 // What the row-movement half of a cache_prepare has to do (decided by the index half).
 // evicted-row blocks of the DMA evict transmitter that may be on their way at once
 constexpr int DMA_BLOCKS = 4;
-struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0; bool arrived = false; };
+struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0, transit_base = -1; bool arrived = false; };
 struct PresortRec {
     bool valid = false;
     const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
@@ -92,7 +92,8 @@ struct fc_cache {
     // The lists an index half writes and its row-movement half reads exist twice, so that the index half of the next
     // batch can run while the rows of the current one still move: lset = the set of the latest index half.
     int lset = 0;
-    int32_t* lists[2][5] = {};      // per set: miss_ranks, vslot, fill_slots, fill_src, vrank (vrank: kernel-store transmitters only)
+    int32_t* lists[2][7] = {};      // per set: miss_ranks, vslot, fill_slots, fill_src (DMA evict), vrank (unless it lives
+                                    // with the DMA block), and with FC_DIRTY_TRACK the dirty victims' ranks and slots
     hipEvent_t ev_move_done[2] = {nullptr, nullptr};   // the row movement that read set k has finished
     hipStream_t move_stream[2] = {nullptr, nullptr};   // the stream it ran on (nullptr: none yet)
     // cache_plan_next also fetches the planned batch's missing rows ahead of time, on the stream `pf`, into the
@@ -146,6 +147,16 @@ struct fc_cache {
     float* stage_pin = nullptr;     // staged mode: pinned block (both directions)
     int32_t* list_pin = nullptr;    // staged mode: pinned copies of miss / victim rank lists [2*C]
 
+    // FC_DIRTY_TRACK: dirty[s] = 1 once the backward pass has updated slot s since it was loaded.  out_rank / out_slot:
+    // the victims that are written back (all of them without the flag).
+    bool dirty_track = false;
+    uint8_t* dirty = nullptr;       // [C]
+    int32_t* dcount = nullptr;      // dirty victims per tile of 1024 victims
+    int32_t* dctl = nullptr;        // pinned: {dirty victims in all, ticket}
+    int32_t dticket = 0;
+    const int32_t* out_rank = nullptr;
+    const int32_t* out_slot = nullptr;
+
     // DMA evict transmitter (FC_EVICT_DMA): evicted-row blocks leave HBM by hipMemcpyAsync on the side stream and
     // are scattered into the host table by worker threads; up to DMA_BLOCKS blocks in flight.  While a row's newest copy is
     // still on its way, rank_slot[rank] = -2 - (block * staging_rows + row in block) ("in transit") and a miss
@@ -196,7 +207,7 @@ namespace fc {
 inline void use_list_set(fc_cache* c, int k) {
     c->lset = k;
     c->miss_ranks = c->lists[k][0]; c->vslot = c->lists[k][1]; c->fill_slots = c->lists[k][2]; c->fill_src = c->lists[k][3];
-    if (!c->dma_evict) c->vrank = c->lists[k][4];
+    if (c->lists[k][4]) c->vrank = c->lists[k][4];
 }
 
 // ---- error plumbing ----
@@ -242,7 +253,7 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
 int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, const int32_t* dst_idx, int64_t dst_rows,
                      const float* src, const int32_t* src_idx, int64_t src_rows, int64_t rows, int max_blocks);
 // host[slot_rank[s]] = cache[s] for every resident slot, written straight into the mapped host table.
-int launch_flush_rows(fc_cache* c, hipStream_t s);
+int launch_flush_rows(fc_cache* c, hipStream_t s);   // FC_DIRTY_TRACK: dirty rows only
 // miss fill that honours transit marks: row j comes from the host table or from a device-side evicted-row block
 // dst == nullptr: into the cache slots fill_slots[j]; else into row j of the block dst (of dst_rows rows)
 int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst = nullptr, int64_t dst_rows = 0, int max_blocks = 0);

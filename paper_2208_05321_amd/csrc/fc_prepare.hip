@@ -387,6 +387,76 @@ __global__ __launch_bounds__(FREE_THREADS) void k_free_assign(int32_t* slot_rank
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// FC_DIRTY_TRACK: of the victims (vrank[j], vslot[j]), j < need, keep those whose slot is dirty, in order.
+//     a) dirty victims per tile of DIRTY_TILE victims;  b) each tile writes its dirty victims after those of the
+//     tiles before it, clears the dirty flags of all its victims, and (DMA evict transmitter) marks the kept rows as
+//     in transit at their place in the block; the last tile reports the total to the host.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int DIRTY_TILE = 1024;
+constexpr int DIRTY_THREADS = 256;
+constexpr int DIRTY_PER = DIRTY_TILE / DIRTY_THREADS;
+
+__global__ __launch_bounds__(DIRTY_THREADS) void k_dirty_count(const int32_t* __restrict__ vslot, int need, int C,
+                                                              const uint8_t* __restrict__ dirty, int32_t* __restrict__ dcount) {
+    __shared__ int red[DIRTY_THREADS / 64];
+    const int j0 = blockIdx.x * DIRTY_TILE + threadIdx.x * DIRTY_PER;
+    int e = 0;
+    for (int k = 0; k < DIRTY_PER; ++k) {
+        const int j = j0 + k;
+        if (j < need) { const int s = vslot[j]; if ((unsigned)s < (unsigned)C && dirty[s]) ++e; }
+    }
+    const int w = wave_sum(e);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < DIRTY_THREADS / 64; ++k) t += red[k];
+        dcount[blockIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(DIRTY_THREADS) void k_dirty_keep(const int32_t* __restrict__ vrank, const int32_t* __restrict__ vslot,
+                                                             int need, int C, uint8_t* dirty, const int32_t* __restrict__ dcount,
+                                                             int32_t* __restrict__ out_rank, int32_t* __restrict__ out_slot,
+                                                             int32_t* rank_slot, int transit_base, int32_t* dctl, int ticket) {
+    __shared__ int lds[DIRTY_THREADS / 64];
+    int part = 0;
+    for (int g = threadIdx.x; g < (int)blockIdx.x; g += DIRTY_THREADS) part += dcount[g];
+    int base;
+    (void)block_excl_scan<DIRTY_THREADS>(part, base, lds);
+    const int j0 = blockIdx.x * DIRTY_TILE + threadIdx.x * DIRTY_PER;
+    unsigned m = 0;
+    int sl[DIRTY_PER];
+    for (int k = 0; k < DIRTY_PER; ++k) {
+        const int j = j0 + k;
+        sl[k] = -1;
+        if (j < need) {
+            const int s = vslot[j];
+            if ((unsigned)s < (unsigned)C) { sl[k] = s; if (dirty[s]) m |= 1u << k; }
+        }
+    }
+    int tot;
+    int o = base + block_excl_scan<DIRTY_THREADS>(__popc(m), tot, lds);
+    for (int k = 0; k < DIRTY_PER; ++k) {
+        if (sl[k] < 0) continue;
+        if ((m >> k) & 1u) {
+            const int r = vrank[j0 + k];
+            out_rank[o] = r;
+            out_slot[o] = sl[k];
+            if (transit_base >= 0) rank_slot[r] = -2 - (transit_base + o);
+            ++o;
+        }
+        dirty[sl[k]] = 0;                  // the slot is empty now; whatever is loaded next equals its host copy
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        dctl[0] = base + tot;
+        __threadfence_system();
+        *reinterpret_cast<volatile int32_t*>(&dctl[1]) = ticket;   // the count first, then the ticket the host polls for
+    }
+}
+
 // DMA evict transmitter: the host threads have stored block `base / staging_rows`; rows still marked as in transit
 // in that block are plain "not resident" again (a row re-fetched or re-evicted meanwhile carries another value).
 __global__ __launch_bounds__(256) void k_clear_transit(const int32_t* __restrict__ ranks, int count, int base,
@@ -430,7 +500,7 @@ static int ensure_rbuf(fc_cache* c, int64_t n) {
 static int store_block(fc_cache* c, int64_t off, int64_t rows) {
     FC_HIP(hipEventRecord(c->ev_gather_done, c->pst));
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
-    FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->vrank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, c->evict_blocks));
+    FC_TRY(launch_copy_rows(c, c->side, P_EVICT_STORE, c->host_dev, c->out_rank + off, c->N, c->stage_dev, nullptr, c->staging_rows, rows, c->evict_blocks));
     FC_HIP(hipEventRecord(c->ev_evict_done, c->side));
     c->evict_pending = true;
     return FC_OK;
@@ -441,7 +511,7 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
     for (int64_t off = 0; off < need; off += S) {
         const int64_t rows = need - off < S ? need - off : S;
         if (off > 0) FC_HIP(hipStreamWaitEvent(c->pst, c->ev_evict_done, 0));   // block buffer is being read
-        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->out_slot + off, c->C, rows, 1 << 20));
         if (off + rows >= need && c->evict_early != 1) { *last_off = off; *last_rows = rows; break; }
         FC_TRY(store_block(c, off, rows));
     }
@@ -468,12 +538,12 @@ int dma_quiesce(fc_cache* c, hipStream_t st) {
 // stream, and let the host threads scatter it once it has landed.  Nothing on the caller's stream waits for it.
 static int evict_dma(fc_cache* c, int64_t need, int buf) {
     float* blk = c->stage_dev + (size_t)buf * c->staging_rows * c->D;
-    FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, blk, nullptr, c->staging_rows, c->cache, c->vslot, c->C, need, 1 << 20));
+    FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, blk, nullptr, c->staging_rows, c->cache, c->out_slot, c->C, need, 1 << 20));
     FC_HIP(hipEventRecord(c->ev_gather_done, c->pst));
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
     {
         ProfScope ps(c, P_D2H_BLOCK, c->side);
-        FC_HIP(hipMemcpyAsync(c->vrank_pin[buf], c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, c->side));
+        FC_HIP(hipMemcpyAsync(c->vrank_pin[buf], c->out_rank, (size_t)need * 4, hipMemcpyDeviceToHost, c->side));
         FC_HIP(hipMemcpyAsync(c->blk_pin[buf], blk, (size_t)need * c->D * 4, hipMemcpyDeviceToHost, c->side));
     }
     FC_HIP(hipEventRecord(c->ev_d2h[buf], c->side));
@@ -488,7 +558,7 @@ static int evict_staged(fc_cache* c, int64_t need, const int32_t* vrank_host) {
     const size_t rowb = (size_t)c->D * 4;
     for (int64_t off = 0; off < need; off += S) {
         const int64_t rows = need - off < S ? need - off : S;
-        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->vslot + off, c->C, rows, 1 << 20));
+        FC_TRY(launch_copy_rows(c, c->pst, P_EVICT_GATHER, c->stage_dev, nullptr, c->staging_rows, c->cache, c->out_slot + off, c->C, rows, 1 << 20));
         {
             ProfScope ps(c, P_D2H_BLOCK, c->pst);
             FC_HIP(hipMemcpyAsync(c->stage_pin, c->stage_dev, rows * rowb, hipMemcpyDeviceToHost, c->pst));
@@ -548,7 +618,7 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
                                                                                 (int)(buf * c->staging_rows), c->rank_slot);
             c->blk_rows[buf] = 0;
         }
-        c->vrank = c->vrank_buf[buf];
+        if (!c->dirty_track) c->vrank = c->vrank_buf[buf];
         transit_base = (int)(buf * c->staging_rows);
     }
     const int64_t work = n > num_bags + 1 ? n : num_bags + 1;
@@ -582,7 +652,8 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
         ProfScope ps(c, P_RANK_EMIT, st);
         k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, (uint4*)c->pbits, protect_prev, c->ctl,
                                                            c->moff, c->vtake, c->voff,
-                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C, transit_base, (int)c->staging_rows);
+                                                           c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C,
+                                                           c->dirty_track ? -1 : transit_base, (int)c->staging_rows);
     }
     FC_HIP(hipGetLastError());
     // The planning kernel writes its decision into pinned host memory and, last, this call's ticket: poll for it
@@ -628,7 +699,7 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     FC_HIP(hipEventRecord(c->ev_index_done, st));
     c->last_index_stream = st;
     c->aux = (st == c->pre && !lookahead) ? c->pre : c->pf;
-    mv->valid = true; mv->M = M; mv->need = need; mv->buf = buf;
+    mv->valid = true; mv->M = M; mv->need = need; mv->buf = buf; mv->transit_base = transit_base;
     c->last.n_ids = n;
     c->last.n_unique = h.n_unique;
     c->last.n_hit_unique = h.n_unique - M;
@@ -645,11 +716,40 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
 int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     c->pst = st;
     if (c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_index_done, 0));
-    const int64_t M = mv.M, need = mv.need;
+    const int64_t M = mv.M;
+    int64_t need = mv.need;                    // victims to write back
     const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;
+    c->out_rank = c->vrank; c->out_slot = c->vslot;
+    if (c->dirty_track && need > 0) {
+        // keep the dirty victims only; their number decides the size of the copies below, so the host waits for it
+        const bool dma_block = c->dma_evict && need <= c->staging_rows;
+        int32_t* orank = dma_block ? c->vrank_buf[mv.buf] : c->lists[c->lset][5];
+        int32_t* oslot = c->lists[c->lset][6];
+        const unsigned tiles = (unsigned)cdiv(need, DIRTY_TILE);
+        const int32_t ticket = c->dticket = (c->dticket + 1) & 0x7fffffff;
+        k_dirty_count<<<tiles, DIRTY_THREADS, 0, st>>>(c->vslot, (int)need, (int)c->C, c->dirty, c->dcount);
+        k_dirty_keep<<<tiles, DIRTY_THREADS, 0, st>>>(c->vrank, c->vslot, (int)need, (int)c->C, c->dirty, c->dcount, orank, oslot,
+                                                     c->rank_slot, dma_block ? mv.transit_base : -1, c->dctl, ticket);
+        FC_HIP(hipGetLastError());
+        const volatile int32_t* dv = reinterpret_cast<const volatile int32_t*>(c->dctl);
+        uint64_t spins = 0;
+        while (dv[1] != ticket) {
+            __builtin_ia32_pause();
+            if ((++spins & 0x3FFF) == 0) {
+                const hipError_t q = hipStreamQuery(st);
+                if (q == hipSuccess) break;
+                if (q != hipErrorNotReady) { (void)hipGetLastError(); return FC_ERR_HIP; }
+            }
+        }
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        if (dv[1] != ticket) return FC_ERR_HIP;
+        need = dv[0];
+        c->out_rank = orank; c->out_slot = oslot;
+        c->last.bytes_d2h = need * (int64_t)c->D * 4;
+    }
     if (staged && (M > 0 || need > 0)) {
         if (M > 0) FC_HIP(hipMemcpyAsync(c->list_pin, c->miss_ranks, (size_t)M * 4, hipMemcpyDeviceToHost, st));
-        if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->vrank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
+        if (need > 0) FC_HIP(hipMemcpyAsync(c->list_pin + c->C, c->out_rank, (size_t)need * 4, hipMemcpyDeviceToHost, st));
         FC_HIP(hipStreamSynchronize(st));
     }
     int64_t last_off = 0, last_rows = 0;
@@ -660,7 +760,7 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     bool dma_path = false;
     if (need > 0) {
         if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
-        else if (c->dma_evict && need <= c->staging_rows) { FC_TRY(evict_dma(c, need, mv.buf)); dma_path = true; }
+        else if (c->dma_evict && mv.need <= c->staging_rows) { FC_TRY(evict_dma(c, need, mv.buf)); dma_path = true; }
         else {
             // more victims than one block holds (or no DMA transmitter): store by kernel, block by block; the
             // block buffer is reused from its start, so nothing may be in transit in it any more

@@ -34,10 +34,11 @@ __global__ __launch_bounds__(256) void k_copy_rows(float* __restrict__ dst, cons
     }
 }
 
-// Flush: every resident slot's row goes to its place in the host table.
+// Flush: every resident slot's row (with a dirty array: every dirty one) goes to its place in the host table.
 template <int VEC>
 __global__ __launch_bounds__(256) void k_flush_rows(float* __restrict__ host, const float* __restrict__ cache,
-                                                    const int32_t* __restrict__ slot_rank, int C, int D, int lpr_shift) {
+                                                    const int32_t* __restrict__ slot_rank, int C, int D, int lpr_shift,
+                                                    const uint8_t* __restrict__ dirty) {
     using V = typename Vec<VEC>::T;
     const int lpr = 1 << lpr_shift;
     const int gpb = blockDim.x >> lpr_shift;
@@ -46,6 +47,7 @@ __global__ __launch_bounds__(256) void k_flush_rows(float* __restrict__ host, co
     for (int s = blockIdx.x * gpb + gl; s < C; s += gridDim.x * gpb) {
         const int r = slot_rank[s];
         if (r < 0) continue;
+        if (dirty && !dirty[s]) continue;
         const V* __restrict__ src = reinterpret_cast<const V*>(cache + (size_t)s * D);
         V* __restrict__ d = reinterpret_cast<V*>(host + (size_t)r * D);
         for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = src[cidx];
@@ -134,9 +136,9 @@ int launch_flush_rows(fc_cache* c, hipStream_t s) {
     if (blocks > 8192) blocks = 8192;
     ProfScope ps(c, P_FLUSH_ROWS, s);
     switch (c->vec) {
-        case 4: k_flush_rows<4><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
-        case 2: k_flush_rows<2><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
-        default: k_flush_rows<1><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh); break;
+        case 4: k_flush_rows<4><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh, c->dirty); break;
+        case 2: k_flush_rows<2><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh, c->dirty); break;
+        default: k_flush_rows<1><<<(unsigned)blocks, 256, 0, s>>>(c->host_dev, c->cache, c->slot_rank, (int)c->C, c->D, sh, c->dirty); break;
     }
     FC_HIP(hipGetLastError());
     return FC_OK;

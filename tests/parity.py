@@ -56,22 +56,24 @@ def compare_prepare(gpu, orc, slots_gpu, slots_orc, t, deep=True):
 
 
 def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_every=1, values_every=1, log=None,
-               dma_evict=False):
-    """Drive the GPU library and the oracle over the first `num_batches` batches of workload `w`."""
+               dma_evict=False, dirty_tracking=False, forward_only=lambda t: False, flush_at=()):
+    """Drive the GPU library and the oracle over the first `num_batches` batches of workload `w`.
+    forward_only(t): no backward pass after batch t (matters with dirty_tracking: its rows stay clean);
+    flush_at: batches after which both sides flush."""
     import torch
     from oracle import Oracle
     from paper_2208_05321_amd import FreqCache
 
     dev = torch.device("cuda:0")
     gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, staged=staged, dma_evict=dma_evict)
+                    warm=False, staged=staged, dma_evict=dma_evict, dirty_tracking=dirty_tracking)
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()
     if warm:
         gpu.warm()
-    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm)
-    tot = {"ids": 0, "hit_ids": 0, "miss": 0, "evict": 0}
+    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm, dirty_tracking=dirty_tracking)
+    tot = {"ids": 0, "hit_ids": 0, "miss": 0, "evict": 0, "bytes_d2h": 0}
     for t in range(num_batches):
         ids, offsets = w.batch(t)
         nb = len(offsets) - 1
@@ -86,12 +88,18 @@ def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_eve
         out_d = gpu.embedding_bag_fwd(slots_d, off_d)
         out_o = orc.embedding_bag_fwd(slots_o, offsets)
         assert_close(out_d.cpu().numpy(), out_o, f"batch {t}: pooled output")
-        gpu.embedding_bag_bwd_sgd(slots_d, off_d, grad_d, w.lr)
-        orc.embedding_bag_bwd_sgd(slots_o, offsets, grad, w.lr)
+        if not forward_only(t):
+            gpu.embedding_bag_bwd_sgd(slots_d, off_d, grad_d, w.lr)
+            orc.embedding_bag_bwd_sgd(slots_o, offsets, grad, w.lr)
         if values_every and (t % values_every == 0 or t == num_batches - 1):
             assert_close(gpu.rows(), orc.cache, f"batch {t}: cached rows after SGD")
+        if t in flush_at:
+            gpu.flush()
+            orc.flush()
+            assert_close(host_gpu, host_orc, f"batch {t}: host table after a flush in mid-run")
         s = orc.stats()
         tot["ids"] += s["n_ids"]; tot["hit_ids"] += s["n_hit_ids"]; tot["miss"] += s["n_miss"]; tot["evict"] += s["n_evict"]
+        tot["bytes_d2h"] += s["bytes_d2h"]
         if log:
             log(f"  batch {t}: n={s['n_ids']} unique={s['n_unique']} miss={s['n_miss']} evict={s['n_evict']} ok")
     gpu.check()

@@ -175,3 +175,47 @@ def test_planned_then_plain_prepare_and_flush(torch_cuda):
     assert_close(gpu.host_weight(), orc.host, "host table")
     assert_close(gpu.rows(), orc.cache, "rows")
     gpu.close()
+
+
+# ---- FC_DIRTY_TRACK: only victims updated since they were loaded are written back (a variant beyond the paper) ----
+@pytest.mark.gpu
+@pytest.mark.parametrize("transmitter,staging_rows", [("direct", 0), ("direct", 9), ("dma", 0), ("dma", 700), ("staged", 0), ("staged", 5)])
+@pytest.mark.parametrize("warm", [True, False])
+def test_dirty_tracking(torch_cuda, transmitter, staging_rows, warm):
+    """Mixed run: every third batch is forward-only, so part of the victims are clean.  Slots, lists, maps, bytes written
+    (bit-exact) and all values equal the oracle's dirty-tracking variant; a flush in mid-run cleans every row."""
+    w = make_workload("c2", scale=0.1, cache_ratio=0.015)
+    tot = run_parity(w, 12, warm=warm, staged=transmitter == "staged", dma_evict=transmitter == "dma", staging_rows=staging_rows,
+                     dirty_tracking=True, forward_only=lambda t: t % 3 == 1, flush_at=(6,))
+    assert 0 < tot["bytes_d2h"] < tot["evict"] * w.dim * 4      # some victims were written, some were dropped
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dma", [True, False])
+def test_dirty_tracking_forward_only_writes_nothing(torch_cuda, dma):
+    w = make_workload("c3", scale=0.02, cache_ratio=0.015)
+    tot = run_parity(w, 6, warm=True, dma_evict=dma, dirty_tracking=True, forward_only=lambda t: True)
+    assert tot["evict"] > 0 and tot["bytes_d2h"] == 0
+
+
+@pytest.mark.gpu
+def test_dirty_tracking_always_trained_equals_plain_policy(torch_cuda):
+    """Cold start and a backward pass after every batch: every resident row is dirty, the bytes are those of the paper's policy."""
+    w = make_workload("c5", scale=0.02, cache_ratio=0.015)
+    tot = run_parity(w, 6, warm=False, dma_evict=True, dirty_tracking=True)
+    assert tot["bytes_d2h"] == tot["evict"] * w.dim * 4 > 0
+
+
+@pytest.mark.gpu
+def test_dirty_tracking_refuses_planning_ahead(torch_cuda):
+    import torch
+    from paper_2208_05321_amd import FreqCache, FreqCacheError
+    w = make_workload("c2", scale=0.02, cache_ratio=0.015)
+    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, dma_evict=True, dirty_tracking=True)
+    ids, offsets = w.batch(0)
+    dev = torch.device("cuda:0")
+    for call in (gpu.plan_next, gpu.prepare_next):
+        with pytest.raises(FreqCacheError) as e:
+            call(torch.from_numpy(ids).to(dev), torch.from_numpy(offsets).to(dev))
+        assert e.value.name == "INVALID_ARG"
+    gpu.close()

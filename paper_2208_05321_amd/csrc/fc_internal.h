@@ -65,7 +65,10 @@ struct SortBufs {
 };
 // What the row-movement half of a cache_prepare has to do (decided by the index half).
 // evicted-row blocks of the DMA evict transmitter that may be on their way at once
-constexpr int DMA_BLOCKS = 4;
+#ifndef FC_DMA_BLOCKS
+#define FC_DMA_BLOCKS 4
+#endif
+constexpr int DMA_BLOCKS = FC_DMA_BLOCKS;
 struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0, transit_base = -1; bool arrived = false; };
 struct PresortRec {
     bool valid = false;
@@ -110,7 +113,7 @@ struct fc_cache {
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
                                     // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through
-    int fill_blocks_early = 48;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
+    int fill_blocks_early = 32;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
     int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)
     int evict_early = 2;            // when that kernel starts (tuning: FC_EVICT_EARLY): 0 after the miss fill, under
                                     // forward/backward; 1 right after the gather; 2 together with the miss fill

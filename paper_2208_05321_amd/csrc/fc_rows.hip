@@ -68,23 +68,29 @@ __global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, co
     const int gpb = blockDim.x >> lpr_shift;
     const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
     const int nv = D / VEC;
-    for (int j = blockIdx.x * gpb + gl; j < rows; j += gridDim.x * gpb) {
-        const int di = fill_slots ? fill_slots[j] : j;
-        const int code = fill_src[j];
-        const float* srow;
+    // The three list entries of the NEXT row are requested before this row's data: each is a dependent access of a
+    // microsecond or so, and a row-group that waits for them has no host read in flight.
+    const int stride = gridDim.x * gpb;
+    int j = blockIdx.x * gpb + gl;
+    int di = 0, code = -1, r = 0;
+    if (j < rows) { di = fill_slots ? fill_slots[j] : j; code = fill_src[j]; r = miss_ranks[j]; }
+    while (j < rows) {
+        const int jn = j + stride;
+        int din = 0, coden = -1, rn = 0;
+        if (jn < rows) { din = fill_slots ? fill_slots[jn] : jn; coden = fill_src[jn]; rn = miss_ranks[jn]; }
+        const float* srow = nullptr;
         if (code <= -2) {
             const unsigned k = (unsigned)(-2 - code);
-            if (k >= block_rows) continue;
-            srow = blocks + (size_t)k * D;
-        } else {
-            const int r = miss_ranks[j];
-            if ((unsigned)r >= N) continue;
+            if (k < block_rows) srow = blocks + (size_t)k * D;
+        } else if ((unsigned)r < N) {
             srow = host + (size_t)r * D;
         }
-        if ((unsigned)di >= C) continue;
-        const V* __restrict__ s = reinterpret_cast<const V*>(srow);
-        V* __restrict__ d = reinterpret_cast<V*>(cache + (size_t)di * D);
-        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = s[cidx];
+        if (srow && (unsigned)di < C) {          // never false for lists this library builds
+            const V* __restrict__ sv = reinterpret_cast<const V*>(srow);
+            V* __restrict__ d = reinterpret_cast<V*>(cache + (size_t)di * D);
+            for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = sv[cidx];
+        }
+        j = jn; di = din; code = coden; r = rn;
     }
 }
 

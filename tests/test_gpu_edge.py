@@ -258,3 +258,84 @@ def test_config2_full_size(torch_cuda):
     w = make_workload("c2")
     tot = run_parity(w, 10, warm=True, deep_every=3, values_every=3, log=log)
     assert 0.85 < tot["hit_ids"] / tot["ids"] < 0.95
+
+
+@pytest.mark.parametrize("dma", [True, False])
+def test_planned_degenerate_batches(torch_cuda, dma):
+    """cache_plan_next / cache_advance on the batches where some stage has nothing to do: an empty batch, pure hits
+    (nothing fetched ahead), exactly cache_rows distinct rows (every other row evicted), a refused batch (too many
+    distinct rows: nothing changes, training goes on), a single lookup."""
+    torch = torch_cuda
+    from paper_2208_05321_amd import FreqCacheError
+    w = TinyWorkload(num_rows=3000, dim=24, cache_rows=200, seed=21, multi_hot=False)
+    gpu, orc = make_pair(w, warm=True, dma_evict=dma)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(3)
+
+    def some(k, n):
+        pool = rng.permutation(w.num_rows)[:k]
+        return pool[rng.integers(0, k, size=n)].astype(np.int64)
+
+    def resident(n):
+        res = np.nonzero(orc.rank_slot >= 0)[0]
+        return w.inv_rank[res][rng.integers(0, len(res), size=n)].astype(np.int64)
+
+    kinds = ["some", "empty", "some", "hits", "whole", "too_many", "one", "some", "hits", "some"]
+    ids0 = some(50, 300)
+    off0 = np.arange(len(ids0) + 1, dtype=np.int64)
+    so = orc.prepare(ids0, off0)
+    sd = gpu.prepare(torch.from_numpy(ids0).to(dev), torch.from_numpy(off0).to(dev))
+    compare_prepare(gpu, orc, sd.cpu().numpy(), so, -1)
+    cur = (ids0, off0)
+    keep = []                                        # device buffers stay alive while the library may read them
+    for t, kind in enumerate(kinds):
+        ids, off = cur
+        off_d = torch.from_numpy(off).to(dev)
+        g = rng.standard_normal((len(off) - 1, w.dim)).astype(np.float32)
+        if len(ids):
+            out_d = gpu.embedding_bag_fwd(sd, off_d)
+            assert_close(out_d.cpu().numpy(), orc.embedding_bag_fwd(so, off), f"step {t}: pooled output")
+            gpu.embedding_bag_bwd_sgd(sd, off_d, torch.from_numpy(g).to(dev), 0.05)
+            orc.embedding_bag_bwd_sgd(so, off, g, 0.05)
+        if kind == "some":
+            nxt = some(120, 400)
+        elif kind == "empty":
+            nxt = np.empty(0, dtype=np.int64)
+        elif kind == "hits":
+            nxt = resident(256)
+        elif kind == "whole":
+            nxt = rng.permutation(w.num_rows)[: w.cache_rows].astype(np.int64)
+        elif kind == "too_many":
+            nxt = rng.permutation(w.num_rows)[: w.cache_rows + 1].astype(np.int64)
+        else:
+            nxt = some(1, 1)
+        noff = np.arange(len(nxt) + 1, dtype=np.int64)
+        nxt_d, noff_d = torch.from_numpy(nxt).to(dev), torch.from_numpy(noff).to(dev)
+        keep.append((nxt_d, noff_d, off_d))
+        torch.cuda.synchronize()
+        if kind == "too_many":
+            sr_before = orc.slot_rank
+            with pytest.raises(FreqCacheError) as e:
+                gpu.plan_next(nxt_d, noff_d)
+            assert e.value.name == "BATCH_EXCEEDS_CACHE"
+            gpu.advance()                            # nothing planned: a no-op
+            sr, rs = gpu.state()
+            assert np.array_equal(sr, sr_before) and np.array_equal(rs, orc.rank_slot)
+            assert_close(gpu.rows(), orc.cache, f"step {t}: rows after a refused plan")
+            nxt = nxt[: w.cache_rows // 2]           # the caller splits the batch and goes on
+            noff = np.arange(len(nxt) + 1, dtype=np.int64)
+            nxt_d, noff_d = torch.from_numpy(nxt).to(dev), torch.from_numpy(noff).to(dev)
+            keep.append((nxt_d, noff_d))
+            torch.cuda.synchronize()
+        sd_next = gpu.plan_next(nxt_d, noff_d)
+        gstats = gpu.stats()
+        gpu.advance()
+        so_next = orc.prepare(nxt, noff)
+        assert gstats == orc.stats(), f"step {t} ({kind}): stats {gstats} vs {orc.stats()}"
+        compare_prepare(gpu, orc, sd_next.cpu().numpy(), so_next, t)
+        assert_close(gpu.rows(), orc.cache, f"step {t} ({kind}): cached rows after the rows moved")
+        so, sd, cur = so_next, sd_next, (nxt, noff)
+    gpu.check()
+    gpu.flush(); orc.flush()
+    assert_close(gpu.host_weight(), orc.host, "host table")
+    gpu.close()

@@ -11,7 +11,7 @@ import time
 import numpy as np
 import pytest
 
-from tests.parity import run_parity
+from tests.parity import run_parity, run_parity_planned
 from workloads import make_workload
 
 pytestmark = [pytest.mark.gpu, pytest.mark.slow,
@@ -48,6 +48,17 @@ def test_full_size(name, ratio, batches, dma, host_gb):
     tot = run_parity(w, batches, warm=True, deep_every=batches - 1, values_every=batches - 1, log=log, dma_evict=dma)
     log(f"  totals {tot} in {time.time() - t0:.0f}s")
     assert tot["miss"] > 0
+
+
+@pytest.mark.parametrize("name,batches,host_gb,free", [("c2", 10, 12, False), ("c2", 24, 12, True), ("c4", 4, 130, True)])
+def test_full_size_pipelined_schedule(name, batches, host_gb, free):
+    """The launch configuration bench.py times: DMA evict transmitter, cache_plan_next(t+1) beside batch t's forward /
+    backward, rows fetched ahead of time, cache_advance; `free`: no synchronisation inside the loop, as in the timed
+    region (every slot array, pooled output and the final tables are compared afterwards)."""
+    need_host_gb(host_gb)
+    w = make_workload(name)
+    log(f"{name} pipelined, free-running {free}: rows {w.num_rows} dim {w.dim} cache {w.cache_rows} bags/batch {w.bags_per_batch}")
+    run_parity_planned(w, batches, warm=True, dma_evict=True, free_running=free)
 
 
 def test_config5_uniform_ids_overflow_then_micro_batches():

@@ -84,10 +84,10 @@ def main():
                     help="dma: misses read by kernels from the mapped host table, evicted blocks leave by DMA and are "
                          "scattered by host threads (default); direct: kernels both ways, no host threads; "
                          "staged: the paper's gather / bulk copy / scatter both ways")
-    ap.add_argument("--schedule", choices=("pipelined", "plain", "lookahead"), default="pipelined",
-                    help="pipelined (default): fwd(t), bwd(t), cache_plan_next(t+1), cache_advance - Algorithm 1 as printed, the "
+    ap.add_argument("--schedule", choices=("pipelined", "plain", "lookahead"), default=None,
+                    help="pipelined (default with the dma transmitter): fwd(t), bwd(t), cache_plan_next(t+1), cache_advance - Algorithm 1 as printed, the "
                          "index kernels and the row fetch of batch t+1 run on library streams beside batch t (identical results); "
-                         "plain: cache_prepare(t), fwd(t), bwd(t), everything on one stream; "
+                         "plain (default with the other transmitters): cache_prepare(t), fwd(t), bwd(t), everything on one stream; "
                          "lookahead: cache_prepare_next(t+1) before fwd(t), bwd(t) - a different cache policy (the previous "
                          "batch's rows are protected too), not the headline configuration")
     ap.add_argument("--dirty-tracking", action="store_true",
@@ -206,6 +206,8 @@ def main():
         stats.append(cache.stats())
         cache.advance()
 
+    if args.schedule is None:
+        args.schedule = "pipelined" if args.transmitter == "dma" else "plain"
     if args.schedule == "pipelined" and (args.transmitter == "staged" or args.dirty_tracking or args.forward_only):
         args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter or dirty tracking
     pipelined, lookahead = args.schedule == "pipelined", args.schedule == "lookahead"

@@ -48,6 +48,9 @@ def load_library(path: str | None = None):
     if _lib is not None and path is None:
         return _lib
     p = path or LIB_PATH
+    # torch first: one process must not end up with two HIP runtimes (torch ships its own; whichever is loaded first
+    # serves both, and the streams and device memory handed across the C ABI are torch's)
+    import torch  # noqa: F401
     if not os.path.exists(p):
         raise FileNotFoundError(f"{p} is not built: run `python -m paper_2208_05321_amd.build` first")
     L = ctypes.CDLL(p)

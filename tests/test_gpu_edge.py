@@ -339,3 +339,30 @@ def test_planned_degenerate_batches(torch_cuda, dma):
     gpu.flush(); orc.flush()
     assert_close(gpu.host_weight(), orc.host, "host table")
     gpu.close()
+
+
+def test_two_tables_interleaved(torch_cuda):
+    """Two caches (different shapes and transmitters) driven in turn on one stream: no state is shared between handles."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    wa = TinyWorkload(num_rows=5000, dim=32, cache_rows=300, seed=31, multi_hot=True)
+    wb = TinyWorkload(num_rows=2000, dim=6, cache_rows=150, seed=32, multi_hot=False)
+    ga, oa = make_pair(wa, warm=True, dma_evict=True)
+    gb, ob = make_pair(wb, warm=False)
+    sa = sb = None
+    for t in range(8):
+        for w, g, o in ((wa, ga, oa), (wb, gb, ob)):
+            ids, off = w.batch(t)
+            grad = w.grad(t, len(off) - 1)
+            ids_d, off_d = torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev)
+            so = o.prepare(ids, off)
+            sd = g.prepare(ids_d, off_d)
+            compare_prepare(g, o, sd.cpu().numpy(), so, t)
+            assert_close(g.embedding_bag_fwd(sd, off_d).cpu().numpy(), o.embedding_bag_fwd(so, off), f"batch {t}: pooled output")
+            g.embedding_bag_bwd_sgd(sd, off_d, torch.from_numpy(grad).to(dev), w.lr)
+            o.embedding_bag_bwd_sgd(so, off, grad, w.lr)
+    for g, o in ((ga, oa), (gb, ob)):
+        assert_close(g.rows(), o.cache, "cached rows")
+        g.check(); g.flush(); o.flush()
+        assert_close(g.host_weight(), o.host, "host table")
+        g.close()

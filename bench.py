@@ -92,7 +92,7 @@ def main():
                          "batch's rows are protected too), not the headline configuration")
     ap.add_argument("--dirty-tracking", action="store_true",
                     help="FC_DIRTY_TRACK: only victims updated since they were loaded are written back (a variant beyond the "
-                         "paper; plain schedule only)")
+                         "paper)")
     ap.add_argument("--forward-only", action="store_true",
                     help="no backward pass (inference): a different metric, ids/s through cache prepare + EmbeddingBag forward")
     ap.add_argument("--static-module", action="store_true",
@@ -185,7 +185,8 @@ def main():
                 raise
             refused = True
         cache.embedding_bag_fwd(cur, off_d[t], out=out)
-        cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
+        if not args.forward_only:
+            cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
         cache.advance()
         if refused:
             fallbacks[0] += 1
@@ -201,15 +202,19 @@ def main():
             stats.append(cache.stats())
         nxt = slots2[(t + 1) & 1][: n_ids[t + 1]]
         cache.embedding_bag_fwd(cur, off_d[t], out=out)           # enqueued first: they wait on the GPU for batch t's rows
-        cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
+        if not args.forward_only:
+            cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
         cache.plan_next(ids_d[t + 1], off_d[t + 1], out=nxt)      # index kernels and row fetch of batch t+1 run beside all that
-        stats.append(cache.stats())
+        if not args.dirty_tracking:
+            stats.append(cache.stats())
         cache.advance()
+        if args.dirty_tracking:
+            stats.append(cache.stats())                           # bytes written back are known after the rows moved
 
     if args.schedule is None:
         args.schedule = "pipelined" if args.transmitter == "dma" else "plain"
-    if args.schedule == "pipelined" and (args.transmitter == "staged" or args.dirty_tracking or args.forward_only):
-        args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter or dirty tracking
+    if args.schedule == "pipelined" and args.transmitter == "staged":
+        args.schedule = "plain"          # cache_plan_next is not available with the staged transmitter
     pipelined, lookahead = args.schedule == "pipelined", args.schedule == "lookahead"
     step = step_lookahead if lookahead else (step_planned if pipelined else step_plain)
 

@@ -82,10 +82,11 @@ enum {
                                dirty once embedding_bag_bwd_sgd has updated it since it was loaded; only dirty
                                victims are written back, clean ones are dropped (their copy in the host table is
                                current), and cache_flush writes dirty rows only.  bytes_d2h counts the rows written.
-                               Every other result is unchanged.  cache_prepare then waits on the host once more (for
-                               the number of dirty victims); cache_prepare_next / cache_plan_next are not available
-                               with this flag (FC_ERR_INVALID_ARG): what is dirty is only known after the current
-                               batch's backward pass. */
+                               Every other result is unchanged.  The call that moves the rows (cache_prepare,
+                               cache_prepare_next, or cache_advance after cache_plan_next: what is dirty is only
+                               known after the current batch's backward pass) then waits on the host once more, for
+                               the number of dirty victims; after cache_plan_next, bytes_d2h of cache_last_stats is
+                               final only once cache_advance has returned. */
 };
 
 /* Static module + dynamic module set-up (Sections 4.2, 4.3).

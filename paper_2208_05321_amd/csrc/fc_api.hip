@@ -316,7 +316,7 @@ int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t*
 
 int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                        int32_t* slots_dev) {
-    if (!c || c->dirty_track) return FC_ERR_INVALID_ARG;
+    if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     // everything the caller has enqueued so far (the backward pass of the batch before the current one, and the
     // input buffers of this call) is complete before this call's row movement, or before all of it when the last
@@ -339,7 +339,7 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
 
 int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                     int32_t* slots_dev) {
-    if (!c || (c->flags & FC_TRANSMIT_STAGED) || c->dirty_track) return FC_ERR_INVALID_ARG;
+    if (!c || (c->flags & FC_TRANSMIT_STAGED)) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
     if (c->planned.valid) FC_TRY(cache_advance(c));
     // The index half touches no rows, so it need not wait for the row movement, forward or backward work the caller

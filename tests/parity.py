@@ -114,7 +114,7 @@ def run_parity(w, num_batches, warm=True, staged=False, staging_rows=0, deep_eve
 
 
 def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows=0, deep_every=1, log=None,
-                         free_running=False):
+                         free_running=False, dirty_tracking=False, forward_only=lambda t: False):
     """The look-ahead schedule on both sides: batch t+1 is prepared (protecting batch t's rows) before batch t's
     forward / backward run.  When the two batches do not fit together both sides must refuse, and the batch is then
     prepared the plain way after the backward pass.
@@ -126,13 +126,13 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
 
     dev = torch.device("cuda:0")
     gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, dma_evict=dma_evict)
+                    warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking)
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()
     if warm:
         gpu.warm()
-    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm)
+    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm, dirty_tracking=dirty_tracking)
     data = []
     for t in range(num_batches):
         ids, offsets = w.batch(t)
@@ -143,7 +143,7 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
     so = orc.prepare(data[0][0], data[0][1])
     sd = gpu.prepare(data[0][3], data[0][4])
     compare_prepare(gpu, orc, sd.cpu().numpy(), so, 0)
-    tot = {"lookahead": 0, "fallback": 0, "ids": 0, "hit_ids": orc.stats()["n_hit_ids"], "evict": 0}
+    tot = {"lookahead": 0, "fallback": 0, "ids": 0, "hit_ids": orc.stats()["n_hit_ids"], "evict": 0, "bytes_d2h": 0}
     later = []
     for t in range(num_batches):
         ids, offsets, grad, ids_d, off_d, grad_d = data[t]
@@ -175,8 +175,9 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
             later.append((f"batch {t}: pooled output", out_d, out_o))
         else:
             assert_close(out_d.cpu().numpy(), out_o, f"batch {t}: pooled output")
-        gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
-        orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
+        if not forward_only(t):
+            gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
+            orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
         gpu.advance()
         if refused:
             so_next = orc.prepare(nids, noff)
@@ -185,7 +186,7 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
             tot["fallback"] += 1
         if t + 1 < num_batches:
             s = orc.stats()
-            tot["hit_ids"] += s["n_hit_ids"]; tot["evict"] += s["n_evict"]
+            tot["hit_ids"] += s["n_hit_ids"]; tot["evict"] += s["n_evict"]; tot["bytes_d2h"] += s["bytes_d2h"]
         tot["ids"] += len(ids)
         if log:
             log(f"  batch {t} ok ({'refused, plain prepare' if refused else 'look-ahead'})")
@@ -207,7 +208,8 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
     return tot
 
 
-def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0, free_running=False, plan_first=False):
+def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0, free_running=False, plan_first=False,
+                       dirty_tracking=False, forward_only=lambda t: False):
     """cache_plan_next: the index half of the next batch's prepare runs beside the current batch's forward / backward,
     rows move at cache_advance.  Same policy as plain cache_prepare, so the oracle is simply driven in program order."""
     import torch
@@ -216,13 +218,13 @@ def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0
 
     dev = torch.device("cuda:0")
     gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, dma_evict=dma_evict)
+                    warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking)
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()
     if warm:
         gpu.warm()
-    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm)
+    orc = Oracle(w.freq_rank, host_orc, w.cache_rows, warm=warm, dirty_tracking=dirty_tracking)
     data = []
     for t in range(num_batches):
         ids, offsets = w.batch(t)
@@ -234,6 +236,7 @@ def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0
     sd = gpu.prepare(data[0][3], data[0][4])
     compare_prepare(gpu, orc, sd.cpu().numpy(), so, 0)
     later = []
+    bytes_d2h = 0
     for t in range(num_batches):
         ids, offsets, grad, ids_d, off_d, grad_d = data[t]
         def plan():
@@ -242,12 +245,16 @@ def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0
         if plan_first:          # both call orders are legal
             sd_next, gstats, glists = plan()
         out_d = gpu.embedding_bag_fwd(sd, off_d)
-        gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
+        if not forward_only(t):
+            gpu.embedding_bag_bwd_sgd(sd, off_d, grad_d, w.lr)
         if not plan_first:
             sd_next, gstats, glists = plan()
         gpu.advance()
+        if dirty_tracking and sd_next is not None:
+            gstats = gpu.stats()             # the bytes written back are known once the rows have moved
         out_o = orc.embedding_bag_fwd(so, offsets)
-        orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
+        if not forward_only(t):
+            orc.embedding_bag_bwd_sgd(so, offsets, grad, w.lr)
         if free_running:
             later.append((f"batch {t}: pooled output", out_d, out_o))
         else:
@@ -255,6 +262,7 @@ def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0
         if sd_next is not None:
             so_next = orc.prepare(data[t + 1][0], data[t + 1][1])
             assert gstats == orc.stats(), f"batch {t + 1}: stats {gstats} vs {orc.stats()}"
+            bytes_d2h += gstats["bytes_d2h"]
             if free_running:
                 later.append((f"batch {t + 1}: slots", sd_next, so_next))
             else:
@@ -278,3 +286,4 @@ def run_parity_planned(w, num_batches, warm=True, dma_evict=True, staging_rows=0
     assert np.array_equal(sr, orc.slot_rank) and np.array_equal(rs, orc.rank_slot)
     gpu.close()
     orc.close()
+    return {"bytes_d2h": bytes_d2h}

@@ -207,15 +207,22 @@ def test_dirty_tracking_always_trained_equals_plain_policy(torch_cuda):
 
 
 @pytest.mark.gpu
-def test_dirty_tracking_refuses_planning_ahead(torch_cuda):
-    import torch
-    from paper_2208_05321_amd import FreqCache, FreqCacheError
-    w = make_workload("c2", scale=0.02, cache_ratio=0.015)
-    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, dma_evict=True, dirty_tracking=True)
-    ids, offsets = w.batch(0)
-    dev = torch.device("cuda:0")
-    for call in (gpu.plan_next, gpu.prepare_next):
-        with pytest.raises(FreqCacheError) as e:
-            call(torch.from_numpy(ids).to(dev), torch.from_numpy(offsets).to(dev))
-        assert e.value.name == "INVALID_ARG"
-    gpu.close()
+@pytest.mark.parametrize("dma,free", [(True, False), (False, False), (True, True)])
+def test_dirty_tracking_planned(torch_cuda, dma, free):
+    """FC_DIRTY_TRACK with cache_plan_next / cache_advance: what is dirty is decided at cache_advance, after the current
+    batch's backward pass; bytes written back, the host table and everything else equal the oracle in program order."""
+    from tests.parity import run_parity_planned
+    w = make_workload("c2", scale=0.1, cache_ratio=0.015)
+    tot = run_parity_planned(w, 12, warm=True, dma_evict=dma, free_running=free, dirty_tracking=True,
+                             forward_only=lambda t: t % 3 == 1)
+    assert tot["bytes_d2h"] > 0
+    run_parity_planned(w, 6, warm=False, dma_evict=dma, staging_rows=900, dirty_tracking=True, forward_only=lambda t: t % 2 == 0)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dma", [True, False])
+def test_dirty_tracking_lookahead(torch_cuda, dma):
+    from tests.parity import run_parity_lookahead
+    w = make_workload("c2", scale=0.1, cache_ratio=0.03)
+    tot = run_parity_lookahead(w, 10, warm=True, dma_evict=dma, dirty_tracking=True, forward_only=lambda t: t % 3 == 1)
+    assert tot["lookahead"] > 0 and 0 < tot["bytes_d2h"] < tot["evict"] * w.dim * 4

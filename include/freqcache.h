@@ -104,8 +104,11 @@ enum {
  *                   the store of record: evictions and cache_flush write into it.
  *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3, "the memory
  *                   footprint of the data transmitter is strictly limited"); larger transfers are
- *                   done in several rounds.  0 = default (min(cache_rows, 524288)).
- *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT.
+ *                   done in several rounds.  0 = default (min(cache_rows, 524288)).  Memory, in blocks of
+ *                   staging_rows * dim * 4 bytes: one in HBM by default; with FC_TRANSMIT_STAGED two in
+ *                   HBM and one pinned; with FC_EVICT_DMA four in HBM and four pinned; cache_plan_next
+ *                   adds two in HBM on first use.
+ *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.
  * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous. */

@@ -145,39 +145,43 @@ __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ 
         const int prevk = gl > 0 ? mk[-1] : (beg > 0 ? keys[beg - 1] : -1);
         const int nextk = beg + cnt < n ? (gl + 1 < gpb ? mk[BWD_CHUNK] : keys[beg + cnt]) : -2;
         for (int cidx = lane; cidx < nv; cidx += lpr) {
-            int cur = mk[0];
-            bool open_left = prevk == cur;
+            bool open_left = prevk == mk[0];
             first_kind = 0; has_head = 0; head_slot = -1;
             V acc = vzero(V());
             for (int e0 = 0; e0 < cnt; e0 += BWD_PF) {
-                V g[BWD_PF];
+                // BWD_PF independent gradient rows in flight, and with them the cached row of every run that ends
+                // among these lookups (known from the keys): the update below then finds its operand loaded
+                V g[BWD_PF], w[BWD_PF];
+                bool ends[BWD_PF];
 #pragma unroll
-                for (int k = 0; k < BWD_PF; ++k)  // BWD_PF independent row loads in flight
-                    g[k] = e0 + k < cnt ? reinterpret_cast<const V*>(grad + (size_t)mv[e0 + k] * D)[cidx] : vzero(V());
+                for (int k = 0; k < BWD_PF; ++k) {
+                    const int e = e0 + k;
+                    ends[k] = false;
+                    g[k] = vzero(V()); w[k] = vzero(V());
+                    if (e < cnt) {
+                        g[k] = reinterpret_cast<const V*>(grad + (size_t)mv[e] * D)[cidx];
+                        const int kk = mk[e];
+                        ends[k] = (e + 1 < cnt ? mk[e + 1] : nextk) != kk;
+                        if (ends[k] && kk < C) w[k] = reinterpret_cast<const V*>(cache + (size_t)kk * D)[cidx];
+                    }
+                }
 #pragma unroll
                 for (int k = 0; k < BWD_PF; ++k) {
                     if (e0 + k < cnt) {
-                        const int kk = mk[e0 + k];
-                        if (kk != cur) {              // run of `cur` ends inside the chunk
+                        acc = vadd(acc, g[k]);
+                        if (ends[k]) {                // the run of mk[e0 + k] ends here
+                            const int kk = mk[e0 + k];
                             if (open_left) { pfirst[cidx] = acc; first_kind = 1; }
-                            else if (cur < C) {
-                                V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
-                                row[cidx] = vsgd(row[cidx], acc, lr);
-                            }
+                            else if (kk < C) reinterpret_cast<V*>(cache + (size_t)kk * D)[cidx] = vsgd(w[k], acc, lr);
                             open_left = false;
-                            cur = kk;
                             acc = vzero(V());
                         }
-                        acc = vadd(acc, g[k]);
                     }
                 }
             }
-            const bool open_right = nextk == cur;
-            if (open_left) { pfirst[cidx] = acc; first_kind = open_right ? 2 : 1; }
-            else if (open_right) { plast[cidx] = acc; has_head = 1; head_slot = cur; }
-            else if (cur < C) {
-                V* row = reinterpret_cast<V*>(cache + (size_t)cur * D);
-                row[cidx] = vsgd(row[cidx], acc, lr);
+            if (nextk == mk[cnt - 1]) {               // the last run goes on in the next chunk
+                if (open_left) { pfirst[cidx] = acc; first_kind = 2; }
+                else { plast[cidx] = acc; has_head = 1; head_slot = mk[cnt - 1]; }
             }
         }
     }

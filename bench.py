@@ -95,6 +95,9 @@ def main():
                          "paper)")
     ap.add_argument("--forward-only", action="store_true",
                     help="no backward pass (inference): a different metric, ids/s through cache prepare + EmbeddingBag forward")
+    ap.add_argument("--ids-from-host", action="store_true",
+                    help="side measurement, never the headline: every step also uploads its batch's ids and offsets from "
+                         "pinned host memory inside the timed region (plain and pipelined schedules)")
     ap.add_argument("--static-module", action="store_true",
                     help="instead of the per-batch path, time the GPU build of the static module (id counting + ranking)")
     ap.add_argument("--staging-rows", type=int, default=0)
@@ -157,11 +160,29 @@ def main():
         del a, b
 
     stats = []
+    if args.ids_from_host:
+        # pinned copies of every batch; three device buffers in rotation (a batch is uploaded two steps ahead of its use
+        # in the pipelined schedule, where cache_plan_next reads what was enqueued before the previous cache_advance)
+        ids_h = [x.cpu().pin_memory() for x in ids_d]
+        off_h = [x.cpu().pin_memory() for x in off_d]
+        ring = [(torch.empty(max_n, dtype=torch.int64, device=dev), torch.empty(nb + 1, dtype=torch.int64, device=dev)) for _ in range(3)]
+
+        def upload(t):
+            if t >= len(ids_h):
+                return
+            bi, bo = ring[t % 3]
+            bi[: n_ids[t]].copy_(ids_h[t], non_blocking=True)
+            bo.copy_(off_h[t], non_blocking=True)
+            ids_d[t], off_d[t] = bi[: n_ids[t]], bo
+    else:
+        def upload(t):
+            pass
     slots2 = [slots, torch.empty(max_n, dtype=torch.int32, device=dev)]
     fallbacks = [0]
 
     def step_plain(t):
         s = slots[: n_ids[t]]
+        upload(t)
         cache.prepare(ids_d[t], off_d[t], out=s)
         stats.append(cache.stats())
         cache.embedding_bag_fwd(s, off_d[t], out=out)
@@ -198,9 +219,11 @@ def main():
         # forward / backward and runs beside them on the library's stream, its rows move at cache_advance
         cur = slots2[t & 1][: n_ids[t]]
         if t == 0:
+            upload(0); upload(1)
             cache.prepare(ids_d[0], off_d[0], out=cur)
             stats.append(cache.stats())
         nxt = slots2[(t + 1) & 1][: n_ids[t + 1]]
+        upload(t + 2)
         cache.embedding_bag_fwd(cur, off_d[t], out=out)           # enqueued first: they wait on the GPU for batch t's rows
         if not args.forward_only:
             cache.embedding_bag_bwd_sgd(cur, off_d[t], grads[t % len(grads)], w.lr)
@@ -368,6 +391,7 @@ def main():
                                    "direct": "kernels both ways", "staged": "block transmitter both ways"}[args.transmitter],
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
+        "ids_from_host": bool(args.ids_from_host),
         "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5),
         "roofline": roofline, "host_link": host_link, "kernels": kernels, "cpu_baseline": cpu_baseline,
     }

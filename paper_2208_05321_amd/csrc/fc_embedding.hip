@@ -314,9 +314,10 @@ static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int
     *lds = (size_t)rgpb * BWD_CHUNK * 8 + (size_t)rgpb * sizeof(BwdMeta) + (size_t)rgpb * 2 * c->D * 4;
 }
 
-// Called by cache_prepare / cache_prepare_next once the slots of the batch are on their way: the sort needs nothing
-// but the slots and the bag offsets, so it runs on the auxiliary stream while the missing rows are still crossing
-// the host link.  Two records alternate, so that the sort of the next batch does not disturb the current one's.
+// Called by cache_prepare / cache_prepare_next / cache_plan_next once the slots of the batch are on their way: the
+// sort needs nothing but the slots and the bag offsets, so it runs on a library stream (c->aux) while the missing
+// rows are still crossing the host link.  Two records alternate, so that the sort of the next batch does not
+// disturb the current one's.
 int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags) {
     const int k = c->rec_next;
     c->rec_next ^= 1;

@@ -184,7 +184,7 @@ struct fc_cache {
     int32_t* pmeta = nullptr;       // [groups][4]
     int64_t part_groups = 0;
 
-    // sort of the (slot, bag) pairs started by cache_prepare on the auxiliary stream
+    // sort of the (slot, bag) pairs started by cache_prepare / cache_plan_next on the stream `aux` (one of the two above)
     bool presort = true;            // FC_NO_PRESORT clears it
     hipStream_t aux = nullptr;      // = pf, or pre when cache_plan_next indexes there (pf then fetches rows): the device
                                     // offers four hardware queues, so the library keeps to three streams of its own

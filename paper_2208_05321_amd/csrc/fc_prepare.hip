@@ -519,7 +519,7 @@ static int evict_direct(fc_cache* c, int64_t need, int64_t* last_off, int64_t* l
 }
 
 // DMA evict transmitter: wait until every handed-over block is in the host table and drop all transit marks
-// (afterwards the host table alone is current for every non-resident row, and both blocks are free).
+// (afterwards the host table alone is current for every non-resident row, and all blocks are free).
 int dma_quiesce(fc_cache* c, hipStream_t st) {
     if (!c->dma_evict) return FC_OK;
     pool_wait(c, pool_published(c));
@@ -690,7 +690,7 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
         }
     }
     // every row of the batch has its slot now: write the slots out (the caller then starts sorting them for the
-    // backward pass on the auxiliary stream, where the sort runs while the missing rows cross the host link)
+    // backward pass on a library stream, where the sort runs while the missing rows cross the host link)
     if (n > 0) {
         ProfScope ps(c, P_SLOTS_OUT, st);
         k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);

@@ -142,6 +142,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (flags & FC_EVICT_DMA) c->fill_blocks = 48;
     if (const char* e = getenv("FC_FILL_BLOCKS")) { const int v = atoi(e); if (v >= 1) c->fill_blocks = v; }
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }
+    if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
     c->NB = cdiv(cdiv(N, 32), RT_WORDS);

@@ -33,7 +33,44 @@ __device__ __forceinline__ float4 vsgd(float4 w, float4 g, float lr) {
 // ---------------------------------------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------------------------------------
+// A row-group takes FWD_BAGS consecutive bags.  When each of them holds exactly one lookup (the click-log shape: one id
+// per feature) their rows are independent loads in flight together; otherwise the bags are summed one after the other,
+// four lookups in flight.  The host picks FWD_BAGS = 4 for batches with as many lookups as bags, else 1.
+
 template <int VEC>
+__device__ __forceinline__ bool bag_sum(const float* __restrict__ cache, const int32_t* __restrict__ slots, int64_t beg,
+                                        int64_t end, int n, int C, int D, int lane, int lpr, int nv,
+                                        typename Vec<VEC>::T* __restrict__ o) {
+    using V = typename Vec<VEC>::T;
+    bool bad = false;
+    if (beg < 0) beg = 0;
+    if (end > n) end = n;
+    for (int cidx = lane; cidx < nv; cidx += lpr) {
+        V acc = vzero(V());
+        int64_t i = beg;
+        for (; i + 4 <= end; i += 4) {
+            const int s0 = slots[i], s1 = slots[i + 1], s2 = slots[i + 2], s3 = slots[i + 3];
+            const bool k0 = (unsigned)s0 < (unsigned)C, k1 = (unsigned)s1 < (unsigned)C,
+                       k2 = (unsigned)s2 < (unsigned)C, k3 = (unsigned)s3 < (unsigned)C;
+            bad |= !(k0 && k1 && k2 && k3);
+            const V v0 = k0 ? reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx] : vzero(V());
+            const V v1 = k1 ? reinterpret_cast<const V*>(cache + (size_t)s1 * D)[cidx] : vzero(V());
+            const V v2 = k2 ? reinterpret_cast<const V*>(cache + (size_t)s2 * D)[cidx] : vzero(V());
+            const V v3 = k3 ? reinterpret_cast<const V*>(cache + (size_t)s3 * D)[cidx] : vzero(V());
+            acc = vadd(acc, v0); acc = vadd(acc, v1); acc = vadd(acc, v2); acc = vadd(acc, v3);
+        }
+        for (; i < end; ++i) {
+            const int s0 = slots[i];
+            const bool k0 = (unsigned)s0 < (unsigned)C;
+            bad |= !k0;
+            if (k0) acc = vadd(acc, reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx]);
+        }
+        o[cidx] = acc;
+    }
+    return bad;
+}
+
+template <int VEC, int FWD_BAGS>
 __global__ __launch_bounds__(256) void k_bag_fwd(const float* __restrict__ cache, const int32_t* __restrict__ slots,
                                                  const int64_t* __restrict__ offsets, int num_bags, int n, int C, int D,
                                                  int lpr_shift, float* __restrict__ out, Ctl* ctl) {
@@ -43,32 +80,31 @@ __global__ __launch_bounds__(256) void k_bag_fwd(const float* __restrict__ cache
     const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
     const int nv = D / VEC;
     bool bad = false;
-    for (int b = blockIdx.x * gpb + gl; b < num_bags; b += gridDim.x * gpb) {
-        int64_t beg = offsets[b], end = offsets[b + 1];
-        if (beg < 0) beg = 0;
-        if (end > n) end = n;
-        V* __restrict__ o = reinterpret_cast<V*>(out + (size_t)b * D);
-        for (int cidx = lane; cidx < nv; cidx += lpr) {
-            V acc = vzero(V());
-            int64_t i = beg;
-            for (; i + 4 <= end; i += 4) {
-                const int s0 = slots[i], s1 = slots[i + 1], s2 = slots[i + 2], s3 = slots[i + 3];
-                const bool k0 = (unsigned)s0 < (unsigned)C, k1 = (unsigned)s1 < (unsigned)C,
-                           k2 = (unsigned)s2 < (unsigned)C, k3 = (unsigned)s3 < (unsigned)C;
-                bad |= !(k0 && k1 && k2 && k3);
-                const V v0 = k0 ? reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx] : vzero(V());
-                const V v1 = k1 ? reinterpret_cast<const V*>(cache + (size_t)s1 * D)[cidx] : vzero(V());
-                const V v2 = k2 ? reinterpret_cast<const V*>(cache + (size_t)s2 * D)[cidx] : vzero(V());
-                const V v3 = k3 ? reinterpret_cast<const V*>(cache + (size_t)s3 * D)[cidx] : vzero(V());
-                acc = vadd(acc, v0); acc = vadd(acc, v1); acc = vadd(acc, v2); acc = vadd(acc, v3);
+    for (int64_t b0 = (int64_t)(blockIdx.x * gpb + gl) * FWD_BAGS; b0 < num_bags; b0 += (int64_t)gridDim.x * gpb * FWD_BAGS) {
+        const int nb = num_bags - b0 < FWD_BAGS ? (int)(num_bags - b0) : FWD_BAGS;
+        int64_t off[FWD_BAGS + 1];
+#pragma unroll
+        for (int k = 0; k <= FWD_BAGS; ++k) off[k] = k <= nb ? offsets[b0 + k] : 0;
+        bool single = nb == FWD_BAGS && off[0] >= 0 && off[FWD_BAGS] <= n;
+#pragma unroll
+        for (int k = 0; k < FWD_BAGS; ++k) single = single && off[k + 1] - off[k] == 1;
+        if (single) {
+            int sl[FWD_BAGS];
+#pragma unroll
+            for (int k = 0; k < FWD_BAGS; ++k) sl[k] = slots[off[0] + k];
+            for (int cidx = lane; cidx < nv; cidx += lpr) {
+                V v[FWD_BAGS];
+#pragma unroll
+                for (int k = 0; k < FWD_BAGS; ++k)
+                    v[k] = (unsigned)sl[k] < (unsigned)C ? reinterpret_cast<const V*>(cache + (size_t)sl[k] * D)[cidx] : vzero(V());
+#pragma unroll
+                for (int k = 0; k < FWD_BAGS; ++k) reinterpret_cast<V*>(out + (size_t)(b0 + k) * D)[cidx] = vadd(vzero(V()), v[k]);
             }
-            for (; i < end; ++i) {
-                const int s0 = slots[i];
-                const bool k0 = (unsigned)s0 < (unsigned)C;
-                bad |= !k0;
-                if (k0) acc = vadd(acc, reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx]);
-            }
-            o[cidx] = acc;
+#pragma unroll
+            for (int k = 0; k < FWD_BAGS; ++k) bad |= (unsigned)sl[k] >= (unsigned)C;
+        } else {
+            for (int k = 0; k < nb; ++k)
+                bad |= bag_sum<VEC>(cache, slots, off[k], off[k + 1], n, C, D, lane, lpr, nv, reinterpret_cast<V*>(out + (size_t)(b0 + k) * D));
         }
     }
     if (bad) atomicOr(&ctl->async_flags, EF_BAD_SLOT);
@@ -84,14 +120,19 @@ int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     FC_HIP(hipSetDevice(c->device));
     const int sh = shift_of(c->lpr);
     const int gpb = 256 >> sh;
-    int64_t blocks = cdiv(num_bags, gpb);
+    const int bags_per_group = (n == num_bags && c->fwd_bags > 1) ? c->fwd_bags : 1;
+    int64_t blocks = cdiv(num_bags, (int64_t)gpb * bags_per_group);
     if (blocks > (1 << 20)) blocks = 1 << 20;
     ProfScope ps(c, P_BAG_FWD, c->stream);
-    switch (c->vec) {
-        case 4: k_bag_fwd<4><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
-        case 2: k_bag_fwd<2><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
-        default: k_bag_fwd<1><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl); break;
-    }
+#define FC_FWD(V, B) \
+    k_bag_fwd<V, B><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, slots, offsets, (int)num_bags, (int)n, (int)c->C, c->D, sh, out, c->ctl)
+#define FC_FWD_V(B) \
+    switch (c->vec) { case 4: FC_FWD(4, B); break; case 2: FC_FWD(2, B); break; default: FC_FWD(1, B); break; }
+    if (bags_per_group == 4) { FC_FWD_V(4) }
+    else if (bags_per_group == 2) { FC_FWD_V(2) }
+    else { FC_FWD_V(1) }
+#undef FC_FWD_V
+#undef FC_FWD
     FC_HIP(hipGetLastError());
     return FC_OK;
 }

@@ -110,6 +110,7 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
                                     // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through

@@ -159,24 +159,27 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restri
 // K2b  one workgroup: totals, the call's status, evict_num = numel(miss) - empty slots, output offsets of
 //      every tile's missing ranks, and which tiles give up how many victims (from the top rank down).
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
+// 256 threads: a workgroup this small finds room on a compute unit at once; a 1024-thread one waited up to 200 us for
+// sixteen free wave slots beside the previous batch's forward kernel, with the host waiting for its ticket.
+constexpr int PLAN_THREADS = 256;
+__global__ __launch_bounds__(PLAN_THREADS) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
                                                     HostCtl* hctl, int32_t* __restrict__ moff,
                                                     int32_t* __restrict__ vtake, int32_t* __restrict__ voff,
                                                     const int32_t* __restrict__ hitpart, int nmark, int ticket) {
-    __shared__ int lds[16];
+    __shared__ int lds[PLAN_THREADS / 64];
     const int tid = threadIdx.x;
     int hits;
-    (void)block_excl_scan<1024>(tid < nmark ? hitpart[tid] : 0, hits, lds);   // nmark <= 256
+    (void)block_excl_scan<PLAN_THREADS>(tid < nmark ? hitpart[tid] : 0, hits, lds);   // nmark <= 256
     int carryM = 0, totU = 0;
-    for (int base = 0; base < NB; base += 1024) {
+    for (int base = 0; base < NB; base += PLAN_THREADS) {
         const int b = base + tid;
         const int m = b < NB ? bsum[(size_t)NB + b] : 0;
         const int u = b < NB ? bsum[b] : 0;
         int tot, totu;
-        const int ex = block_excl_scan<1024>(m, tot, lds);
+        const int ex = block_excl_scan<PLAN_THREADS>(m, tot, lds);
         if (b < NB) moff[b] = carryM + ex;
         carryM += tot;
-        (void)block_excl_scan<1024>(u, totu, lds);
+        (void)block_excl_scan<PLAN_THREADS>(u, totu, lds);
         totU += totu;
     }
     const uint32_t ef = ctl->err_flags;
@@ -190,10 +193,10 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
     if (need < 0) need = 0;
     {   // enough evictable rows?  (always, unless the look-ahead protects the previous batch as well)
         int totC = 0;
-        for (int base = 0; base < NB; base += 1024) {
+        for (int base = 0; base < NB; base += PLAN_THREADS) {
             const int b = base + tid;
             int t;
-            (void)block_excl_scan<1024>(b < NB ? bsum[(size_t)2 * NB + b] : 0, t, lds);
+            (void)block_excl_scan<PLAN_THREADS>(b < NB ? bsum[(size_t)2 * NB + b] : 0, t, lds);
             totC += t;
         }
         if (status == FC_OK && need > totC) status = FC_ERR_BATCH_EXCEEDS_CACHE;
@@ -201,11 +204,11 @@ __global__ __launch_bounds__(1024) void k_rank_plan(const int32_t* __restrict__ 
     if (status != FC_OK) need = 0;
     // Victims: walk tiles from the highest ranks down; `above` = evictable rows in tiles of larger rank.
     int carry = 0;
-    for (int base = 0; base < NB; base += 1024) {
+    for (int base = 0; base < NB; base += PLAN_THREADS) {
         const int b = NB - 1 - (base + tid);
         const int cc = b >= 0 ? bsum[(size_t)2 * NB + b] : 0;
         int tot;
-        const int above = carry + block_excl_scan<1024>(cc, tot, lds);
+        const int above = carry + block_excl_scan<PLAN_THREADS>(cc, tot, lds);
         if (b >= 0) {
             int take = 0, off = 0;
             if (above < need && cc > 0) {
@@ -640,7 +643,7 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     }
     {
         ProfScope ps(c, P_RANK_PLAN, st);
-        k_rank_plan<<<1, 1024, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff, c->hitpart, (int)nmark, ticket);
+        k_rank_plan<<<1, PLAN_THREADS, 0, st>>>(c->bsum, (int)c->NB, (int)c->C, c->ctl, c->hctl, c->moff, c->vtake, c->voff, c->hitpart, (int)nmark, ticket);
     }
     // Last batch's evicted rows must have reached the host table before the victim lists and the block buffer
     // are reused and before any of those rows could be fetched again; the kernels above do not care.

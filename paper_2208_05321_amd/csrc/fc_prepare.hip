@@ -162,26 +162,38 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restri
 // 256 threads: a workgroup this small finds room on a compute unit at once; a 1024-thread one waited up to 200 us for
 // sixteen free wave slots beside the previous batch's forward kernel, with the host waiting for its ticket.
 constexpr int PLAN_THREADS = 256;
+constexpr int PLAN_ITEMS = 4;
 __global__ __launch_bounds__(PLAN_THREADS) void k_rank_plan(const int32_t* __restrict__ bsum, int NB, int C, Ctl* ctl,
                                                     HostCtl* hctl, int32_t* __restrict__ moff,
                                                     int32_t* __restrict__ vtake, int32_t* __restrict__ voff,
                                                     const int32_t* __restrict__ hitpart, int nmark, int ticket) {
     __shared__ int lds[PLAN_THREADS / 64];
     const int tid = threadIdx.x;
+    constexpr int CH = PLAN_THREADS * PLAN_ITEMS;          // tiles per round: PLAN_ITEMS consecutive ones per thread
     int hits;
     (void)block_excl_scan<PLAN_THREADS>(tid < nmark ? hitpart[tid] : 0, hits, lds);   // nmark <= 256
-    int carryM = 0, totU = 0;
-    for (int base = 0; base < NB; base += PLAN_THREADS) {
-        const int b = base + tid;
-        const int m = b < NB ? bsum[(size_t)NB + b] : 0;
-        const int u = b < NB ? bsum[b] : 0;
-        int tot, totu;
-        const int ex = block_excl_scan<PLAN_THREADS>(m, tot, lds);
-        if (b < NB) moff[b] = carryM + ex;
+    // forward: output offset of every tile's missing ranks; the totals of used and evictable rows on the way
+    int carryM = 0, accU = 0, accC = 0;
+    for (int base = 0; base < NB; base += CH) {
+        const int b0 = base + tid * PLAN_ITEMS;
+        int m[PLAN_ITEMS], sum = 0;
+#pragma unroll
+        for (int k = 0; k < PLAN_ITEMS; ++k) {
+            const int b = b0 + k;
+            m[k] = b < NB ? bsum[(size_t)NB + b] : 0;
+            if (b < NB) { accU += bsum[b]; accC += bsum[(size_t)2 * NB + b]; }
+            sum += m[k];
+        }
+        int tot;
+        int run = carryM + block_excl_scan<PLAN_THREADS>(sum, tot, lds);
+#pragma unroll
+        for (int k = 0; k < PLAN_ITEMS; ++k)
+            if (b0 + k < NB) { moff[b0 + k] = run; run += m[k]; }
         carryM += tot;
-        (void)block_excl_scan<PLAN_THREADS>(u, totu, lds);
-        totU += totu;
     }
+    int totU, totC;
+    (void)block_excl_scan<PLAN_THREADS>(accU, totU, lds);
+    (void)block_excl_scan<PLAN_THREADS>(accC, totC, lds);
     const uint32_t ef = ctl->err_flags;
     const int nfree = ctl->nfree;
     int status = FC_OK;
@@ -191,32 +203,35 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_rank_plan(const int32_t* __res
     const int M = carryM;
     int need = M - nfree;
     if (need < 0) need = 0;
-    {   // enough evictable rows?  (always, unless the look-ahead protects the previous batch as well)
-        int totC = 0;
-        for (int base = 0; base < NB; base += PLAN_THREADS) {
-            const int b = base + tid;
-            int t;
-            (void)block_excl_scan<PLAN_THREADS>(b < NB ? bsum[(size_t)2 * NB + b] : 0, t, lds);
-            totC += t;
-        }
-        if (status == FC_OK && need > totC) status = FC_ERR_BATCH_EXCEEDS_CACHE;
-    }
+    // enough evictable rows?  (always, unless the look-ahead protects the previous batch as well)
+    if (status == FC_OK && need > totC) status = FC_ERR_BATCH_EXCEEDS_CACHE;
     if (status != FC_OK) need = 0;
     // Victims: walk tiles from the highest ranks down; `above` = evictable rows in tiles of larger rank.
     int carry = 0;
-    for (int base = 0; base < NB; base += PLAN_THREADS) {
-        const int b = NB - 1 - (base + tid);
-        const int cc = b >= 0 ? bsum[(size_t)2 * NB + b] : 0;
+    for (int base = 0; base < NB; base += CH) {
+        const int r0 = base + tid * PLAN_ITEMS;            // position counted from the top tile
+        int cc[PLAN_ITEMS], sum = 0;
+#pragma unroll
+        for (int k = 0; k < PLAN_ITEMS; ++k) {
+            const int b = NB - 1 - (r0 + k);
+            cc[k] = b >= 0 ? bsum[(size_t)2 * NB + b] : 0;
+            sum += cc[k];
+        }
         int tot;
-        const int above = carry + block_excl_scan<PLAN_THREADS>(cc, tot, lds);
-        if (b >= 0) {
-            int take = 0, off = 0;
-            if (above < need && cc > 0) {
-                take = min(cc, need - above);
-                off = need - above - take;   // victims are listed in ascending rank
+        int above = carry + block_excl_scan<PLAN_THREADS>(sum, tot, lds);
+#pragma unroll
+        for (int k = 0; k < PLAN_ITEMS; ++k) {
+            const int b = NB - 1 - (r0 + k);
+            if (b >= 0) {
+                int take = 0, off = 0;
+                if (above < need && cc[k] > 0) {
+                    take = min(cc[k], need - above);
+                    off = need - above - take;   // victims are listed in ascending rank
+                }
+                vtake[b] = take;
+                voff[b] = off;
+                above += cc[k];
             }
-            vtake[b] = take;
-            voff[b] = off;
         }
         carry += tot;
     }

@@ -8,8 +8,10 @@
  * turns the batch's ids into row indices of the cached weight (Algorithm 1,
  * PrepareCache), runs the EmbeddingBag-sum forward on the cached rows and applies the
  * sparse SGD update to them (Section 4.3, last step of the workflow; synchronous
- * updates, Section 2.2).  Every step runs in hand-written HIP kernels on the caller's
- * stream; a second, library-owned stream carries the write-back of evicted rows.
+ * updates, Section 2.2).  Every step runs in hand-written HIP kernels, on the caller's
+ * stream unless stated otherwise: three library-owned streams carry the write-back of
+ * evicted rows, the sort the backward pass needs, and -- with cache_plan_next or
+ * cache_prepare_next -- the next batch's index work and row fetch beside the current batch.
  *
  * Conventions
  *   - every function returns FC_OK (0) or a negative FC_ERR_* code; nothing throws or aborts;

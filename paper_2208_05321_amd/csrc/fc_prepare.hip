@@ -607,6 +607,23 @@ static int fill_staged(fc_cache* c, int64_t M, const int32_t* miss_host) {
     return FC_OK;
 }
 
+// A kernel writes a small record into pinned host memory and, last, a ticket; the host polls for the ticket (cheaper
+// than an event round trip, and the kernels enqueued behind it keep the GPU busy meanwhile).  Falls back to the
+// stream's status so that a failed launch cannot hang the caller.
+static int wait_for_ticket(const volatile int32_t* ticket_word, int32_t ticket, hipStream_t st) {
+    uint64_t spins = 0;
+    while (*ticket_word != ticket) {
+        __builtin_ia32_pause();
+        if ((++spins & 0x3FFF) == 0) {
+            const hipError_t q = hipStreamQuery(st);
+            if (q == hipSuccess) break;                          // stream drained: the record is there
+            if (q != hipErrorNotReady) { (void)hipGetLastError(); return FC_ERR_HIP; }
+        }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return *ticket_word == ticket ? FC_OK : FC_ERR_HIP;
+}
+
 // Index half of Algorithm 1: every decision (unique rows, misses, victims, slot assignment, both maps, the slots
 // of the batch) and no row movement.  Fills *mv with what prepare_move has to do.
 int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
@@ -674,22 +691,11 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
                                                            c->dirty_track ? -1 : transit_base, (int)c->staging_rows);
     }
     FC_HIP(hipGetLastError());
-    // The planning kernel writes its decision into pinned host memory and, last, this call's ticket: poll for it
-    // (cheaper than an event round trip, and the kernels enqueued behind it keep the GPU busy meanwhile).
+    // the planning kernel's decision
     HostCtl h;
     {
         const volatile int32_t* hv = reinterpret_cast<const volatile int32_t*>(c->hctl);
-        uint64_t spins = 0;
-        while (hv[7] != ticket) {
-            __builtin_ia32_pause();
-            if ((++spins & 0x3FFF) == 0) {
-                const hipError_t q = hipStreamQuery(st);
-                if (q == hipSuccess) break;                          // stream drained: the record is there
-                if (q != hipErrorNotReady) { (void)hipGetLastError(); return FC_ERR_HIP; }
-            }
-        }
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);
-        if (hv[7] != ticket) return FC_ERR_HIP;
+        FC_TRY(wait_for_ticket(hv + 7, ticket, st));
         h.status = hv[0]; h.n_unique = hv[1]; h.n_miss = hv[2]; h.need = hv[3]; h.hit_ids = hv[4]; h.nfree = hv[5];
         h.async_flags = hv[6]; h.ticket = hv[7];
     }
@@ -750,17 +756,7 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
                                                      c->rank_slot, dma_block ? mv.transit_base : -1, c->dctl, ticket);
         FC_HIP(hipGetLastError());
         const volatile int32_t* dv = reinterpret_cast<const volatile int32_t*>(c->dctl);
-        uint64_t spins = 0;
-        while (dv[1] != ticket) {
-            __builtin_ia32_pause();
-            if ((++spins & 0x3FFF) == 0) {
-                const hipError_t q = hipStreamQuery(st);
-                if (q == hipSuccess) break;
-                if (q != hipErrorNotReady) { (void)hipGetLastError(); return FC_ERR_HIP; }
-            }
-        }
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);
-        if (dv[1] != ticket) return FC_ERR_HIP;
+        FC_TRY(wait_for_ticket(dv + 1, ticket, st));
         need = dv[0];
         c->out_rank = orank; c->out_slot = oslot;
         c->last.bytes_d2h = need * (int64_t)c->D * 4;

@@ -22,6 +22,22 @@ __device__ __forceinline__ float4 vzero(float4) { return make_float4(0.f, 0.f, 0
 __device__ __forceinline__ float vadd(float a, float b) { return a + b; }
 __device__ __forceinline__ float2 vadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
 __device__ __forceinline__ float4 vadd(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+// Streaming accesses (data touched once per step: pooled outputs, output gradients) are marked non-temporal so that
+// they do not push the cached rows, which forward and backward both touch, out of the memory-side cache.
+__device__ __forceinline__ void nt_store(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void nt_store(float2* p, float2 v) { __builtin_nontemporal_store(v.x, &p->x); __builtin_nontemporal_store(v.y, &p->y); }
+__device__ __forceinline__ void nt_store(float4* p, float4 v) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    v4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+}
+__device__ __forceinline__ float nt_load(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float2 nt_load(const float2* p) { return make_float2(__builtin_nontemporal_load(&p->x), __builtin_nontemporal_load(&p->y)); }
+__device__ __forceinline__ float4 nt_load(const float4* p) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
 // row - lr * g with the product rounded before the subtraction (no fused multiply-add)
 __device__ __forceinline__ float sgd1(float w, float g, float lr) { return __fsub_rn(w, __fmul_rn(lr, g)); }
 __device__ __forceinline__ float vsgd(float w, float g, float lr) { return sgd1(w, g, lr); }
@@ -65,7 +81,7 @@ __device__ __forceinline__ bool bag_sum(const float* __restrict__ cache, const i
             bad |= !k0;
             if (k0) acc = vadd(acc, reinterpret_cast<const V*>(cache + (size_t)s0 * D)[cidx]);
         }
-        o[cidx] = acc;
+        nt_store(&o[cidx], acc);
     }
     return bad;
 }
@@ -98,7 +114,7 @@ __global__ __launch_bounds__(256) void k_bag_fwd(const float* __restrict__ cache
                 for (int k = 0; k < FWD_BAGS; ++k)
                     v[k] = (unsigned)sl[k] < (unsigned)C ? reinterpret_cast<const V*>(cache + (size_t)sl[k] * D)[cidx] : vzero(V());
 #pragma unroll
-                for (int k = 0; k < FWD_BAGS; ++k) reinterpret_cast<V*>(out + (size_t)(b0 + k) * D)[cidx] = vadd(vzero(V()), v[k]);
+                for (int k = 0; k < FWD_BAGS; ++k) nt_store(&reinterpret_cast<V*>(out + (size_t)(b0 + k) * D)[cidx], vadd(vzero(V()), v[k]));
             }
 #pragma unroll
             for (int k = 0; k < FWD_BAGS; ++k) bad |= (unsigned)sl[k] >= (unsigned)C;
@@ -200,7 +216,7 @@ __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ 
                     ends[k] = false;
                     g[k] = vzero(V()); w[k] = vzero(V());
                     if (e < cnt) {
-                        g[k] = reinterpret_cast<const V*>(grad + (size_t)mv[e] * D)[cidx];
+                        g[k] = nt_load(&reinterpret_cast<const V*>(grad + (size_t)mv[e] * D)[cidx]);
                         const int kk = mk[e];
                         ends[k] = (e + 1 < cnt ? mk[e + 1] : nextk) != kk;
                         if (ends[k] && kk < C) w[k] = reinterpret_cast<const V*>(cache + (size_t)kk * D)[cidx];

@@ -164,7 +164,8 @@ int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
 // 2 = lies wholly inside a longer run.
 struct BwdMeta { int first_kind, has_head, head_slot, pad; };
 
-template <int VEC>
+// STREAM: every gradient row is read exactly once (one lookup per bag) -> non-temporal loads
+template <int VEC, bool STREAM>
 __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ keys, const int32_t* __restrict__ vals,
                                                     int n, int C, const float* __restrict__ grad, float* cache, int D,
                                                     int lpr_shift, float lr, float* __restrict__ part,
@@ -216,7 +217,8 @@ __global__ __launch_bounds__(256) void k_bwd_reduce(const int32_t* __restrict__ 
                     ends[k] = false;
                     g[k] = vzero(V()); w[k] = vzero(V());
                     if (e < cnt) {
-                        g[k] = nt_load(&reinterpret_cast<const V*>(grad + (size_t)mv[e] * D)[cidx]);
+                        const V* gp = &reinterpret_cast<const V*>(grad + (size_t)mv[e] * D)[cidx];
+                        g[k] = STREAM ? nt_load(gp) : *gp;
                         const int kk = mk[e];
                         ends[k] = (e + 1 < cnt ? mk[e + 1] : nextk) != kk;
                         if (ends[k] && kk < C) w[k] = reinterpret_cast<const V*>(cache + (size_t)kk * D)[cidx];
@@ -422,11 +424,13 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     {
         ProfScope ps(c, P_BWD_REDUCE, st);
         BwdMeta* bm = reinterpret_cast<BwdMeta*>(c->pmeta);
-        switch (c->vec) {
-            case 4: k_bwd_reduce<4><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
-            case 2: k_bwd_reduce<2><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
-            default: k_bwd_reduce<1><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm); break;
-        }
+#define FC_BWD(V, S) \
+        k_bwd_reduce<V, S><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm)
+#define FC_BWD_V(S) \
+        switch (c->vec) { case 4: FC_BWD(4, S); break; case 2: FC_BWD(2, S); break; default: FC_BWD(1, S); break; }
+        if (n == num_bags) { FC_BWD_V(true) } else { FC_BWD_V(false) }
+#undef FC_BWD_V
+#undef FC_BWD
     }
     {
         ProfScope ps(c, P_BWD_FIXUP, st);

@@ -9,6 +9,13 @@ template <int VEC> struct Vec;
 template <> struct Vec<1> { using T = float; };
 template <> struct Vec<2> { using T = float2; };
 template <> struct Vec<4> { using T = float4; };
+__device__ __forceinline__ float nt_load_row(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float2 nt_load_row(const float2* p) { return make_float2(__builtin_nontemporal_load(&p->x), __builtin_nontemporal_load(&p->y)); }
+__device__ __forceinline__ float4 nt_load_row(const float4* p) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
 
 // dst[dst_idx ? dst_idx[j] : j] = src[src_idx ? src_idx[j] : j] for j in [0, rows); row length D floats.
 // lpr (power of two, <= 64) consecutive lanes own one row; a lane moves VEC floats per access.
@@ -30,7 +37,9 @@ __global__ __launch_bounds__(256) void k_copy_rows(float* __restrict__ dst, cons
         if ((unsigned)di >= dst_rows || (unsigned)si >= src_rows) continue;   // never true for lists this library builds
         const V* __restrict__ s = reinterpret_cast<const V*>(src + (size_t)si * D);
         V* __restrict__ d = reinterpret_cast<V*>(dst + (size_t)di * D);
-        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = s[cidx];
+        // the evicted rows and the rows of an arrival block are read for the last time here: non-temporal loads keep them
+        // from displacing the cached rows in the memory-side cache
+        for (int cidx = lane; cidx < nv; cidx += lpr) d[cidx] = KIND == 1 ? s[cidx] : nt_load_row(&s[cidx]);
     }
 }
 

@@ -139,7 +139,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (staging_rows > C) staging_rows = C;
     c->staging_rows = staging_rows;
     if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }
-    if (flags & FC_EVICT_DMA) c->fill_blocks = 48;
+    if (flags & FC_EVICT_DMA) c->fill_blocks = 40;
     if (const char* e = getenv("FC_FILL_BLOCKS")) { const int v = atoi(e); if (v >= 1) c->fill_blocks = v; }
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }

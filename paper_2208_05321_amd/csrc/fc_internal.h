@@ -112,7 +112,7 @@ struct fc_cache {
     bool evict_pending = false;
     int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
-    int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 48 with FC_EVICT_DMA:
+    int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 40 with FC_EVICT_DMA:
                                     // ~200 KB of reads in flight fill the link and still let the DMA engine's writes through
     int fill_blocks_early = 32;     // the same for rows fetched ahead of time by cache_plan_next (tuning: FC_FILL_BLOCKS_EARLY)
     int evict_blocks = 1024;        // workgroups of the host-table store kernel (tuning: FC_EVICT_BLOCKS)

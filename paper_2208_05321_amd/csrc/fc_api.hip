@@ -2,6 +2,8 @@
 // The per-batch work lives in fc_prepare.hip (Algorithm 1) and fc_embedding.hip (EmbeddingBag + SGD).
 #include "fc_internal.h"
 
+#include <stdio.h>
+
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -68,6 +70,8 @@ static int reset_state(fc_cache* c, bool warm) {
     for (hipStream_t x : {c->pre, c->pf, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
     c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr; c->pf_dep = nullptr;
+    c->fetch_timed[0] = c->fetch_timed[1] = false; c->last_copy_buf = -1;
+    for (bool& b : c->copy_timed) b = false;
     for (PresortRec& r : c->rec) r.valid = false;
     if (c->dma_evict) { pool_wait(c, pool_published(c)); for (int64_t& r : c->blk_rows) r = 0; }
     const int64_t words = c->NB * RT_WORDS;
@@ -89,6 +93,8 @@ static int reset_state(fc_cache* c, bool warm) {
 
 static void destroy(fc_cache* c) {
     if (!c) return;
+    if (c->tune_early && getenv("FC_TUNE_REPORT"))
+        fprintf(stderr, "freqcache: early-fetch workgroups settled at %d (fetch / copy ratio %.3f)\n", c->fill_blocks_early, c->tune_ratio);
     (void)hipSetDevice(c->device);
     if (c->stream || c->side) (void)hipDeviceSynchronize();
     pool_destroy(c);
@@ -104,8 +110,10 @@ static void destroy(fc_cache* c) {
     if (c->dctl) (void)hipHostFree(c->dctl);
     for (int k = 0; k < 2; ++k) {
         if (c->arrive[k]) (void)hipFree(c->arrive[k]);
-        if (c->ev_arrive[k]) (void)hipEventDestroy(c->ev_arrive[k]);
+        for (hipEvent_t e : {c->ev_arrive[k], c->ev_fetch_a[k], c->ev_fetch_b[k]}) if (e) (void)hipEventDestroy(e);
     }
+    for (int b = 0; b < DMA_BLOCKS; ++b)
+        for (hipEvent_t e : {c->ev_copy_a[b], c->ev_copy_b[b]}) if (e) (void)hipEventDestroy(e);
     for (void* p : {(void*)c->freq_rank, (void*)c->rank_slot, (void*)c->slot_rank, (void*)c->cache, (void*)c->ubits,
                     (void*)c->rbits, (void*)c->tcount, (void*)c->hitpart, (void*)c->bsum, (void*)c->moff, (void*)c->vtake, (void*)c->voff,
                     (void*)c->rbuf,
@@ -141,7 +149,9 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_EVICT_BLOCKS")) { const int v = atoi(e); if (v >= 1 && v <= 4096) c->evict_blocks = v; }
     if (flags & FC_EVICT_DMA) c->fill_blocks = 40;
     if (const char* e = getenv("FC_FILL_BLOCKS")) { const int v = atoi(e); if (v >= 1) c->fill_blocks = v; }
-    if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }
+    if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) { c->fill_blocks_early = v; c->tune_early = false; } }
+    if (const char* e = getenv("FC_FILL_BLOCKS_EARLY_START")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }   // still tuned
+    c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
@@ -221,6 +231,12 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+    if (c->dma_evict) {
+        for (int k = 0; k < 2; ++k) { FC_HIP(hipEventCreate(&c->ev_fetch_a[k])); FC_HIP(hipEventCreate(&c->ev_fetch_b[k])); }
+        for (int b = 0; b < DMA_BLOCKS; ++b) { FC_HIP(hipEventCreate(&c->ev_copy_a[b])); FC_HIP(hipEventCreate(&c->ev_copy_b[b])); }
+    } else {
+        c->tune_early = false;
+    }
     FC_HIP(hipMemcpy(c->freq_rank, freq_rank, (size_t)N * 4, hipMemcpyHostToDevice));
     if (c->dma_evict) {
         int threads = 8;
@@ -234,6 +250,34 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
 
 using namespace fc;
 
+// Duration in us between two timing events if both have completed, else a negative number.
+static float elapsed_us(hipEvent_t a, hipEvent_t b) {
+    if (hipEventQuery(b) != hipSuccess) { (void)hipGetLastError(); return -1.f; }
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, a, b) != hipSuccess) { (void)hipGetLastError(); return -1.f; }
+    return ms * 1e3f;
+}
+
+// One step of the controller described at fc_cache::tune_early: the fetch that last used list set k against the newest
+// finished block copy (no copy at all: the fetch has the link to itself and may take what it can use).
+static void tune_fetch_grid(fc_cache* c, int k) {
+    if (!c->fetch_timed[k]) return;
+    const float f_us = elapsed_us(c->ev_fetch_a[k], c->ev_fetch_b[k]);
+    if (f_us <= 0.f) return;
+    float d_us = -1.f;
+    if (c->last_copy_buf >= 0)
+        for (int i = 0; i < DMA_BLOCKS && d_us <= 0.f; ++i) {
+            const int b = (c->last_copy_buf - i + DMA_BLOCKS) % DMA_BLOCKS;
+            if (c->copy_timed[b]) d_us = elapsed_us(c->ev_copy_a[b], c->ev_copy_b[b]);
+        }
+    const float r = d_us > 0.f ? f_us / d_us : 2.f;
+    c->tune_ratio = c->tune_ratio <= 0.f ? r : 0.75f * c->tune_ratio + 0.25f * r;
+    if (++c->tune_count < 6) return;
+    c->tune_count = 0;
+    if (c->tune_ratio < 0.98f && c->fill_blocks_early > 8) --c->fill_blocks_early;
+    else if (c->tune_ratio > 1.06f && c->fill_blocks_early < c->fill_blocks_early_max) ++c->fill_blocks_early;
+}
+
 // cache_plan_next: the planned batch's missing rows into the arrival block of its list set, on the stream pf
 static int fetch_early(fc_cache* c, int64_t M) {
     const int k = c->lset;
@@ -241,10 +285,17 @@ static int fetch_early(fc_cache* c, int64_t M) {
         (void)hipGetLastError(); c->arrive[k] = nullptr;
         return FC_OK;                  // no room for the block: the rows are fetched at cache_advance instead
     }
+    if (c->tune_early) tune_fetch_grid(c, k);
     FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
     if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
-    if (c->dma_evict) FC_TRY(launch_fill_rows(c, c->pf, M, c->arrive[k], c->staging_rows, c->fill_blocks_early));
-    else FC_TRY(launch_copy_rows(c, c->pf, P_MISS_FILL, c->arrive[k], nullptr, c->staging_rows, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
+    if (c->dma_evict) {
+        FC_HIP(hipEventRecord(c->ev_fetch_a[k], c->pf));
+        FC_TRY(launch_fill_rows(c, c->pf, M, c->arrive[k], c->staging_rows, c->fill_blocks_early));
+        FC_HIP(hipEventRecord(c->ev_fetch_b[k], c->pf));
+        c->fetch_timed[k] = true;
+    } else {
+        FC_TRY(launch_copy_rows(c, c->pf, P_MISS_FILL, c->arrive[k], nullptr, c->staging_rows, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
+    }
     FC_HIP(hipEventRecord(c->ev_arrive[k], c->pf));
     c->planned.arrived = true;
     return FC_OK;

@@ -173,6 +173,20 @@ struct fc_cache {
     int64_t blk_rows[fc::DMA_BLOCKS] = {};        // rows whose transit marks are still set, per block
     hipEvent_t ev_d2h[fc::DMA_BLOCKS] = {};
     hipEvent_t pf_dep = nullptr;                  // what the next early fetch of missing rows has to wait for
+    // The early fetch (zero-copy reads) and the evicted-row block copy (DMA writes) share the host link all the time in
+    // the pipelined schedule; how they split it depends on the fetch's workgroup count, and a step is worst when the
+    // block copy is the slower one (the host then waits for block buffers).  Unless FC_FILL_BLOCKS_EARLY pins it, that
+    // count follows the measured durations: timing events around both, a smoothed ratio fetch / copy, one workgroup
+    // fewer every few steps while the copy is the slower one, one more (up to the default, which suits steps that are
+    // not bound by the link) while the fetch is clearly the slower one.
+    bool tune_early = true;
+    int fill_blocks_early_max = 32;
+    hipEvent_t ev_fetch_a[2] = {nullptr, nullptr}, ev_fetch_b[2] = {nullptr, nullptr};
+    hipEvent_t ev_copy_a[fc::DMA_BLOCKS] = {}, ev_copy_b[fc::DMA_BLOCKS] = {};
+    bool fetch_timed[2] = {false, false}, copy_timed[fc::DMA_BLOCKS] = {};
+    int last_copy_buf = -1;
+    float tune_ratio = 0.f;
+    int tune_count = 0;
     uint64_t dma_seq = 0;                         // blocks handed to the pool so far
 
     float* host = nullptr;          // pinned, rank-ordered table

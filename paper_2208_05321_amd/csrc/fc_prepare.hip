@@ -561,8 +561,10 @@ static int evict_dma(fc_cache* c, int64_t need, int buf) {
     FC_HIP(hipStreamWaitEvent(c->side, c->ev_gather_done, 0));
     {
         ProfScope ps(c, P_D2H_BLOCK, c->side);
+        if (c->ev_copy_a[buf]) FC_HIP(hipEventRecord(c->ev_copy_a[buf], c->side));
         FC_HIP(hipMemcpyAsync(c->vrank_pin[buf], c->out_rank, (size_t)need * 4, hipMemcpyDeviceToHost, c->side));
         FC_HIP(hipMemcpyAsync(c->blk_pin[buf], blk, (size_t)need * c->D * 4, hipMemcpyDeviceToHost, c->side));
+        if (c->ev_copy_b[buf]) { FC_HIP(hipEventRecord(c->ev_copy_b[buf], c->side)); c->copy_timed[buf] = true; c->last_copy_buf = buf; }
     }
     FC_HIP(hipEventRecord(c->ev_d2h[buf], c->side));
     c->blk_rows[buf] = need;

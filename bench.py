@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch at config 2 from rocprofv3 --pmc (2 x FETCH_SIZE + WRITE_SIZE, scale factors from a plain copy;
 # profiles/c2_pmc_fetch_write_size.md); only quoted when the workload is exactly config 2.
-PMC_TRAFFIC_C2 = {"bwd_reduce": 314.9e6, "bag_fwd": 331.9e6}
+PMC_TRAFFIC_C2 = {"bwd_reduce": 313.6e6, "bag_fwd": 312.2e6}
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 LINK_PEAK_GBS = 64.0       # PCIe Gen5 x16, per direction, nominal
 

@@ -134,6 +134,59 @@ static void destroy(fc_cache* c) {
     delete c;
 }
 
+// ---- library streams on hardware queues of their own -------------------------------------------------------------
+// A process has few hardware queues (four by default) and the runtime hands them to streams as they are created, so
+// two streams may share one, and work on them then runs one after the other whatever the events say.  The pipelined
+// schedule needs the caller's stream and the three library streams to run side by side.  Which streams share a queue
+// cannot be asked, but it can be seen: a kernel that spins for a fixed time on one stream, a trivial kernel on the
+// other; if the trivial one finishes long before the spinning one, the two streams are served side by side.
+__global__ void k_spin(long long ticks, int* sink) {
+    const long long t0 = wall_clock64();                  // constant 100 MHz counter
+    while (wall_clock64() - t0 < ticks) { }
+    if (sink && ticks < 0) *sink = 1;
+}
+__global__ void k_touch(int* sink) { if (sink && threadIdx.x == 12345) *sink = 1; }
+
+// true: work on b runs while work on a is busy.  On any error: true (take the stream, nothing to be gained by being picky).
+static bool run_side_by_side(hipStream_t a, hipStream_t b) {
+    hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;
+    bool ok = true;
+    if (hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess && hipEventCreate(&e2) == hipSuccess) {
+        const long long spin_ticks = 30000;               // 300 us
+        (void)hipEventRecord(e0, a);
+        k_spin<<<1, 64, 0, a>>>(spin_ticks, nullptr);
+        (void)hipEventRecord(e1, a);
+        k_touch<<<1, 64, 0, b>>>(nullptr);
+        (void)hipEventRecord(e2, b);
+        float spin_ms = 0.f, other_ms = 0.f;
+        if (hipStreamSynchronize(a) == hipSuccess && hipStreamSynchronize(b) == hipSuccess &&
+            hipEventElapsedTime(&spin_ms, e0, e1) == hipSuccess && hipEventElapsedTime(&other_ms, e0, e2) == hipSuccess)
+            ok = other_ms < 0.5f * spin_ms;
+    }
+    (void)hipGetLastError();
+    for (hipEvent_t e : {e0, e1, e2}) if (e) (void)hipEventDestroy(e);
+    return ok;
+}
+
+// Three non-blocking streams that run side by side with the caller's stream and with each other, chosen among a few
+// candidates; whatever is left over when the candidates run out is taken as it comes.
+static int make_library_streams(fc_cache* c) {
+    hipStream_t* want[3] = {&c->side, &c->pre, &c->pf};
+    std::vector<hipStream_t> rejected;
+    int have = 0;
+    for (int tries = 0; tries < 12 && have < 3; ++tries) {
+        hipStream_t s = nullptr;
+        FC_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        bool good = run_side_by_side(c->stream, s);
+        for (int k = 0; k < have && good; ++k) good = run_side_by_side(*want[k], s);
+        if (good) *want[have++] = s; else rejected.push_back(s);
+    }
+    while (have < 3 && !rejected.empty()) { *want[have++] = rejected.back(); rejected.pop_back(); }
+    for (hipStream_t s : rejected) (void)hipStreamDestroy(s);
+    while (have < 3) FC_HIP(hipStreamCreateWithFlags(want[have++], hipStreamNonBlocking));
+    return FC_OK;
+}
+
 static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float* host_weight, int64_t staging_rows,
                   int32_t flags, void* hip_stream, fc_cache* c) {
     FC_HIP(hipGetDevice(&c->device));
@@ -222,9 +275,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
             (void)hipGetLastError(); return FC_ERR_OOM_PINNED;
         }
     }
-    FC_HIP(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-    FC_HIP(hipStreamCreateWithFlags(&c->pre, hipStreamNonBlocking));
-    FC_HIP(hipStreamCreateWithFlags(&c->pf, hipStreamNonBlocking));
+    FC_TRY(make_library_streams(c));
     c->aux = c->pf;
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;

@@ -113,7 +113,17 @@ enum {
  *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.
- * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous. */
+ * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous (it also runs a few
+ * sub-millisecond test kernels on hip_stream to find library streams that run beside it).
+ * Tuning knobs, read from the environment at this call (defaults suit an MI355X on a PCIe Gen5 x16 link):
+ *   FC_FILL_BLOCKS        workgroups of the miss fill (40 with FC_EVICT_DMA, else 1024)
+ *   FC_FILL_BLOCKS_EARLY  workgroups of cache_plan_next's early row fetch, fixed (default: starts at 32 and follows the
+ *                         measured fetch / block-copy durations); FC_FILL_BLOCKS_EARLY_START only moves the start
+ *   FC_EVICT_BLOCKS, FC_EVICT_EARLY   width and start of the host-table store kernel (transmitter without FC_EVICT_DMA)
+ *   FC_SCATTER_THREADS    host threads of FC_EVICT_DMA (8)
+ *   FC_FWD_BAGS           bags per row-group of the forward kernel for one-lookup bags: 1, 2 or 4 (4)
+ *   FC_MARK_IPT           ids per thread of the marking kernel (2)
+ *   FC_TUNE_REPORT        if set, cache_destroy prints where the early-fetch workgroup count settled */
 int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_t* freq_rank_host,
                  float* host_weight, int64_t staging_rows, int32_t flags, void* hip_stream, fc_cache** out);
 

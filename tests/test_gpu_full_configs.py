@@ -50,7 +50,7 @@ def test_full_size(name, ratio, batches, dma, host_gb):
     assert tot["miss"] > 0
 
 
-@pytest.mark.parametrize("name,batches,host_gb,free", [("c2", 10, 12, False), ("c2", 24, 12, True), ("c4", 4, 130, True)])
+@pytest.mark.parametrize("name,batches,host_gb,free", [("c2", 10, 12, False), ("c2", 24, 12, True), ("c4", 4, 130, True), ("c5", 3, 130, True)])
 def test_full_size_pipelined_schedule(name, batches, host_gb, free):
     """The launch configuration bench.py times: DMA evict transmitter, cache_plan_next(t+1) beside batch t's forward /
     backward, rows fetched ahead of time, cache_advance; `free`: no synchronisation inside the loop, as in the timed

@@ -3,7 +3,8 @@
 
 A step = cache_prepare + embedding_bag_fwd + embedding_bag_bwd_sgd on one batch of synthetic ids
 (config 2 by default: 26 features in one 10M x 128 fp32 table, batch 16,384 x 26 one-hot ids, cache 1.5%).
-Prints ONE JSON line; see the design doc for the byte model behind `roofline`.
+Prints ONE JSON line.  The byte model behind `roofline` (what one launch of each kernel has to move) is the `model`
+table in profile_pass below.
 """
 from __future__ import annotations
 
@@ -281,7 +282,7 @@ def main():
             u_m = float(np.mean([s["n_unique"] for s in pstats]))
             m_m = float(np.mean([s["n_miss"] for s in pstats]))
             e_m = float(np.mean([s["n_evict"] for s in pstats]))
-            # algorithmic bytes per launch (what the step must move, "byte model")
+            # algorithmic bytes per launch: what the step must move whatever the implementation (R = bytes per row)
             model = {
                 "remap_mark": n_m * (8 + 4 + 4 + 4) + (nb + 1) * 8,            # id, idx_map entry, resident bit word, rank out
                 "rank_count": nw * 4 * 2,

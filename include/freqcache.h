@@ -104,8 +104,8 @@ enum {
  *                   cache_warm) -- or a pointer to page-locked, GPU-mapped memory
  *                   (hipHostMalloc / a pinned torch tensor) that outlives the handle.  The table is
  *                   the store of record: evictions and cache_flush write into it.
- *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3, "the memory
- *                   footprint of the data transmitter is strictly limited"); larger transfers are
+ *   staging_rows    bound, in rows, of the transmitter's block buffers (Section 4.3 keeps the transmitter's
+ *                   memory footprint bounded); larger transfers are
  *                   done in several rounds.  0 = default (min(cache_rows, 524288)).  Memory, in blocks of
  *                   staging_rows * dim * 4 bytes: one in HBM by default; with FC_TRANSMIT_STAGED two in
  *                   HBM and one pinned; with FC_EVICT_DMA four in HBM and four pinned; cache_plan_next
@@ -148,7 +148,7 @@ int cache_warm(fc_cache* c);
 int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
                   int32_t* slots_dev);
 
-/* Look-ahead (the paper's Future Work: an input-id prefetch that looks ahead to more input ids): Algorithm 1 for the
+/* Look-ahead (the paper's Future Work section proposes prefetching on the ids of coming batches): Algorithm 1 for the
  * NEXT batch, issued while the batch of the latest cache_prepare / cache_prepare_next is still being trained on.
  * Same arguments, results and errors as cache_prepare, with two differences:
  *   - the rows of that previous batch are protected from eviction as well (the backlist of Algorithm 1 is the union

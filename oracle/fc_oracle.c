@@ -5,7 +5,7 @@
  * used only by the tests, by the smoke check and by the benchmark's CPU
  * baseline; the GPU library never calls it and shares no code with it.
  *
- * Two layers of definition (paper Section 2.2 "Synchronous Embedding Updates",
+ * Two layers of definition (paper Section 2.2 on synchronous embedding updates,
  * Section 4.3, Algorithm 1):
  *   - VALUES (pooled outputs, updated rows, flushed table): with synchronous
  *     updates the cache is invisible; results equal EmbeddingBag-sum + SGD run
@@ -20,7 +20,7 @@
  * `rank`, the frequency rank, Section 4.2); the CPU Weight `host` holds row
  * cpu_row_idx; the CUDA Cached Weight `cache` holds `C` rows; cache_idx_map is
  * kept as two mutually inverse arrays, slot_rank[gpu_row_idx] = cpu_row_idx
- * (-1 = empty slot, Algorithm 1's "-1 ... indicates id not in GPU") and
+ * (-1 = empty slot, the marker Algorithm 1 uses for a row that is not on the GPU) and
  * rank_slot[cpu_row_idx] = gpu_row_idx (-1 = not resident), because the
  * algorithm indexes the map in both directions.
  *
@@ -149,8 +149,8 @@ int fco_create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float*
 
 /* Algorithm 1: PrepareCache + PrepareCPURowIdxOnGPU. slots_out[n] receives gpu_row_idx per input id.
  * protect_prev = 0: the algorithm as printed (the backlist is the current batch).
- * protect_prev = 1: look-ahead variant (the paper's Future Work: "an input-id-prefetch method that looks ahead to
- *   more input ids"): this batch is prepared while the previously prepared batch is still being trained on, so the
+ * protect_prev = 1: look-ahead variant (the paper's Future Work section proposes prefetching on the ids of coming
+ *   batches): this batch is prepared while the previously prepared batch is still being trained on, so the
  *   backlist is the union of both batches' rows.  If that leaves fewer evictable rows than needed the call fails
  *   with BATCH_EXCEEDS_CACHE and changes nothing. */
 static int prepare_core(fco* o, const int64_t* ids, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out,

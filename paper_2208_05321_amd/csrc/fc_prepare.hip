@@ -6,8 +6,8 @@
 //   ubits  rows used by this batch        -> unique() is "which bits are set", ascending for free
 //   rbits  rows resident in HBM           -> missing = ubits & ~rbits, evictable = rbits & ~ubits
 // and the empty slots are read off the slot->rank map: the i-th missing rank takes the i-th empty slot.
-// "The evict_num largest cpu_row_idx not used by the batch" (LFU by static frequency rank) is the top
-// evict_num set bits of (rbits & ~ubits): a suffix count over bitmap tiles finds the threshold tile.
+// The victims of Section 4.3 (LFU by static frequency rank: of the rows the batch does not use, the evict_num with
+// the largest cpu_row_idx) are the top evict_num set bits of (rbits & ~ubits): a suffix count over bitmap tiles finds the threshold tile.
 #include "fc_internal.h"
 
 #include <omp.h>

@@ -1,7 +1,7 @@
 // Host side of the DMA evict transmitter: a small pool of threads that scatters evicted-row blocks, once their
 // device -> host copy has landed in pinned memory, into the frequency-ordered host table
-// (paper Section 4.3, data transmitter: "blocks are transferred ... and scattered to the corresponding position
-// of the target memory").  Blocks are numbered 1, 2, ... in hand-over order and scattered one after the other, so a
+// (paper Section 4.3, data transmitter: rows travel as one block and are put in their places on the receiving side).
+// Blocks are numbered 1, 2, ... in hand-over order and scattered one after the other, so a
 // row evicted twice ends with its newer value.
 #include "fc_internal.h"
 

@@ -175,7 +175,9 @@ class FreqCache:
         return slots
 
     def plan_next(self, ids, offsets, out=None):
-        """cache_plan_next: index half of cache_prepare for the next batch, ahead of time; rows move at advance()."""
+        """cache_plan_next: index half of cache_prepare for the next batch, ahead of time; rows move at advance().
+        ids / offsets must be complete, or enqueued on the cache's stream before the previous advance() / prepare():
+        the library's streams do not wait for work enqueued after that call (see include/freqcache.h)."""
         torch = self._torch
         n = ids.numel()
         assert ids.dtype == torch.int64 and offsets.dtype == torch.int64 and ids.is_cuda and offsets.is_cuda

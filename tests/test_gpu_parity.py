@@ -226,3 +226,59 @@ def test_dirty_tracking_lookahead(torch_cuda, dma):
     w = make_workload("c2", scale=0.1, cache_ratio=0.03)
     tot = run_parity_lookahead(w, 10, warm=True, dma_evict=dma, dirty_tracking=True, forward_only=lambda t: t % 3 == 1)
     assert tot["lookahead"] > 0 and 0 < tot["bytes_d2h"] < tot["evict"] * w.dim * 4
+
+
+@pytest.mark.gpu
+def test_planned_inputs_uploaded_one_step_ahead(torch_cuda):
+    """The ordering contract of cache_plan_next: ids / offsets that are copied to the device on the caller's stream (no
+    host synchronisation) before the previous cache_advance are seen complete by the library's streams."""
+    torch = torch_cuda
+    from oracle import Oracle
+    from paper_2208_05321_amd import FreqCache
+    w = make_workload("c2", scale=0.2, cache_ratio=0.015)
+    dev = torch.device("cuda:0")
+    T = 12
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, dma_evict=True, stream=st)
+        host = gpu.host_weight()
+        w.host_table(out=host)
+        gpu.warm()
+        orc = Oracle(w.freq_rank, host.copy(), w.cache_rows, warm=True)
+        batches = [w.batch(t) for t in range(T + 2)]
+        pinned = [(torch.from_numpy(i).pin_memory(), torch.from_numpy(o).pin_memory()) for i, o in batches]
+        nmax = max(len(i) for i, _ in batches)
+        ring = [(torch.empty(nmax, dtype=torch.int64, device=dev), torch.empty(len(batches[0][1]), dtype=torch.int64, device=dev)) for _ in range(3)]
+        grads = [torch.from_numpy(w.grad(t, len(batches[t][1]) - 1)).to(dev) for t in range(T)]
+        slots_buf = [torch.empty(nmax, dtype=torch.int32, device=dev) for _ in range(3)]
+        dev_in = {}
+
+        def upload(t):                                   # asynchronous, on the cache's stream
+            bi, bo = ring[t % 3]
+            n = len(batches[t][0])
+            bi[:n].copy_(pinned[t][0], non_blocking=True)
+            bo.copy_(pinned[t][1], non_blocking=True)
+            dev_in[t] = (bi[:n], bo)
+
+        torch.cuda.synchronize()
+        upload(0); upload(1)
+        cur = gpu.prepare(dev_in[0][0], dev_in[0][1], out=slots_buf[0][: len(batches[0][0])])
+        got = [cur.clone()]
+        for t in range(T):
+            upload(t + 2)                                # before this step's advance(): ready for the next step's plan_next
+            out = gpu.embedding_bag_fwd(cur, dev_in[t][1])
+            gpu.embedding_bag_bwd_sgd(cur, dev_in[t][1], grads[t], w.lr)
+            nxt = gpu.plan_next(dev_in[t + 1][0], dev_in[t + 1][1], out=slots_buf[(t + 1) % 3][: len(batches[t + 1][0])])
+            gpu.advance()
+            got.append(nxt.clone())                      # on the cache's stream, after advance
+            cur = nxt
+        torch.cuda.synchronize()
+        for t in range(T + 1):
+            so = orc.prepare(*batches[t])
+            assert np.array_equal(got[t].cpu().numpy(), so), f"batch {t}: slots"
+            if t < T:
+                orc.embedding_bag_fwd(so, batches[t][1])
+                orc.embedding_bag_bwd_sgd(so, batches[t][1], w.grad(t, len(batches[t][1]) - 1), w.lr)
+        gpu.flush(); orc.flush()
+        assert_close(host, orc.host, "host table")
+        gpu.close()

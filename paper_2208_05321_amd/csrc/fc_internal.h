@@ -16,8 +16,9 @@ constexpr int RT_THREADS = 256;
 constexpr int RT_WORDS = RT_THREADS * 4;
 // Radix sort of (slot, bag) pairs for the backward pass.
 constexpr int RS_THREADS = 256;
-constexpr int RS_ITEMS = 16;
-constexpr int RS_TILE = RS_THREADS * RS_ITEMS;
+constexpr int RS_ITEMS = 8;                      // keys per thread; RS_ITEMS_WIDE when a pass has more than 512 digits
+constexpr int RS_ITEMS_WIDE = 16;
+constexpr int RS_TILE = RS_THREADS * RS_ITEMS;    // the smaller tile: sizes the per-tile digit tables
 constexpr int RS_MAX_BITS = 11;
 // Consecutive sorted lookups reduced by one row-group in the backward pass.
 #ifndef FC_BWD_CHUNK

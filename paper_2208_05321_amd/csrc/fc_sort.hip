@@ -14,7 +14,6 @@ __device__ __forceinline__ int first_key(const int32_t* __restrict__ slots, int 
 
 // bag of lookup i: the largest b with offsets[b] <= i
 __device__ __forceinline__ int bag_of(const int64_t* __restrict__ offsets, int num_bags, int i) {
-    if (i < num_bags && offsets[i] == i && offsets[i + 1] == (int64_t)i + 1) return i;   // one id per bag
     int lo = 0, hi = num_bags;
     while (hi - lo > 1) {
         const int mid = (int)(((int64_t)lo + hi) >> 1);
@@ -31,51 +30,63 @@ __device__ __forceinline__ int load_key(const int32_t* __restrict__ keys_in, int
     return keys_in[i];
 }
 
-template <int SRC>
+template <int SRC, int ITEMS>
 __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restrict__ keys_in, int n, int limit, int shift,
                                                           int radix_bits, int nblk, int32_t* __restrict__ ghist,
                                                           uint32_t* flags) {
     __shared__ int h[1 << RS_MAX_BITS];
     const int radix = 1 << radix_bits, mask = radix - 1;
+    const int tile0 = blockIdx.x * (RS_THREADS * ITEMS);
+    // all of the tile's keys are requested before anything waits for one (a lane beyond n rereads the last key)
+    int key[ITEMS];
+    bool bad = false;
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it)
+        key[it] = load_key<SRC>(keys_in, min(tile0 + it * RS_THREADS + (int)threadIdx.x, n - 1), limit, bad);
     for (int d = threadIdx.x; d < radix; d += RS_THREADS) h[d] = 0;
     __syncthreads();
-    const int tile0 = blockIdx.x * RS_TILE;
-    bool bad = false;
-#pragma unroll 4
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * RS_THREADS + threadIdx.x;
-        if (i < n) {
-            const int k = load_key<SRC>(keys_in, i, limit, bad);
-            atomicAdd(&h[(k >> shift) & mask], 1);
-        }
-    }
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it)
+        if (tile0 + it * RS_THREADS + (int)threadIdx.x < n) atomicAdd(&h[(key[it] >> shift) & mask], 1);
     __syncthreads();
     for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)d * nblk + blockIdx.x] = h[d];
     if (bad && flags) atomicOr(flags, EF_BAD_SLOT);
 }
 
 // One wavefront per digit: exclusive scan of that digit's counts over the tiles; the digit total goes to dtot.
+// The counts of RS_SCAN_K * 64 tiles are requested together before the first one is waited for.
+constexpr int RS_SCAN_K = 8;
 __global__ __launch_bounds__(256) void k_sort_scan(int32_t* ghist, int nblk, int radix, int32_t* __restrict__ dtot) {
     const int d = (blockIdx.x * 256 + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     if (d >= radix) return;
+    int32_t* row = ghist + (size_t)d * nblk;
     int carry = 0;
-    for (int b0 = 0; b0 < nblk; b0 += 64) {
-        const int b = b0 + lane;
-        const int v = b < nblk ? ghist[(size_t)d * nblk + b] : 0;
-        int x = v;
+    for (int c0 = 0; c0 < nblk; c0 += 64 * RS_SCAN_K) {
+        int v[RS_SCAN_K];
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            int y = __shfl_up(x, o);
-            if (lane >= o) x += y;
+        for (int k = 0; k < RS_SCAN_K; ++k) {
+            const int b = c0 + k * 64 + lane;
+            const int t = row[min(b, nblk - 1)];
+            v[k] = b < nblk ? t : 0;
         }
-        if (b < nblk) ghist[(size_t)d * nblk + b] = carry + x - v;
-        carry += __shfl(x, 63);
+#pragma unroll
+        for (int k = 0; k < RS_SCAN_K; ++k) {
+            const int b = c0 + k * 64 + lane;
+            int x = v[k];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                int y = __shfl_up(x, o);
+                if (lane >= o) x += y;
+            }
+            if (b < nblk) row[b] = carry + x - v[k];
+            carry += __shfl(x, 63);
+        }
     }
     if (lane == 0) dtot[d] = carry;
 }
 
-template <int SRC>
+template <int SRC, int ITEMS>
 __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __restrict__ keys_in,
                                                              const int32_t* __restrict__ vals_in,
                                                              const int64_t* __restrict__ offsets, int num_bags, int n,
@@ -90,6 +101,23 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
     __shared__ int lds[NW];
     const int radix = 1 << radix_bits, mask = radix - 1;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tile0 = blockIdx.x * (RS_THREADS * ITEMS) + w * (64 * ITEMS);
+    // The tile's keys and values are requested first, all together, so that their latency runs beside the digit
+    // bases below.  A lane beyond n rereads element n-1 and is masked out later.
+    int key[ITEMS], val[ITEMS];
+    int64_t o0[ITEMS], o1[ITEMS];
+    bool bad = false;
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int i = min(tile0 + it * 64 + lane, n - 1);
+        key[it] = load_key<SRC>(keys_in, i, limit, bad);
+        if (SRC == SORT_SRC_SLOTS) {           // bag of lookup i, first guess: one lookup per bag
+            const int g = min(i, num_bags - 1);
+            o0[it] = offsets[g];
+            o1[it] = offsets[g + 1];
+        } else if (SRC == SORT_SRC_COUNTS) val[it] = i;
+        else val[it] = vals_in[i];
+    }
     {   // digit bases: exclusive scan of the digit totals, plus this tile's offset within the digit
         const int per = (radix + RS_THREADS - 1) / RS_THREADS;
         const int d0 = tid * per;
@@ -110,22 +138,20 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
         }
     }
     __syncthreads();
-    const int tile0 = blockIdx.x * RS_TILE + w * (RS_TILE / NW);
-    const uint64_t lt = (1ull << lane) - 1ull;
-    int key[RS_ITEMS], val[RS_ITEMS], lrank[RS_ITEMS];
-    bool bad = false;
+    if (SRC == SORT_SRC_SLOTS) {
 #pragma unroll
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * 64 + lane;
-        const bool valid = i < n;
-        int k = 0, v = 0;
-        if (valid) {
-            k = load_key<SRC>(keys_in, i, limit, bad);
-            if (SRC == SORT_SRC_SLOTS) v = bag_of(offsets, num_bags, i);
-            else if (SRC == SORT_SRC_COUNTS) v = i;
-            else v = vals_in[i];
+        for (int it = 0; it < ITEMS; ++it) {
+            const int i = min(tile0 + it * 64 + lane, n - 1);
+            const int g = min(i, num_bags - 1);
+            val[it] = (o0[it] <= i && i < o1[it]) ? g : bag_of(offsets, num_bags, i);
         }
-        const int d = (k >> shift) & mask;
+    }
+    const uint64_t lt = (1ull << lane) - 1ull;
+    int lrank[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const bool valid = tile0 + it * 64 + lane < n;
+        const int d = (key[it] >> shift) & mask;
         uint64_t peers = __ballot(valid);
         for (int b = 0; b < radix_bits; ++b) {
             const bool one = (d >> b) & 1;
@@ -137,8 +163,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
         if (valid) old = wc[w][d];
         if (valid && before == 0) wc[w][d] = old + __popcll(peers);
         lrank[it] = old + before;
-        key[it] = k;
-        val[it] = v;
     }
     __syncthreads();
     for (int d = tid; d < radix; d += RS_THREADS) {
@@ -148,9 +172,8 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < RS_ITEMS; ++it) {
-        const int i = tile0 + it * 64 + lane;
-        if (i < n) {
+    for (int it = 0; it < ITEMS; ++it) {
+        if (tile0 + it * 64 + lane < n) {
             const int d = (key[it] >> shift) & mask;
             const int dest = base[d] + wc[w][d] + lrank[it];
             keys_out[dest] = key[it];
@@ -160,13 +183,14 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
 }
 
 
-template <int SRC>
+template <int SRC, int ITEMS>
 static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
-                        int shift, int rb, int nblk) {
+                        int shift, int rb) {
     const int radix = 1 << rb;
+    const int nblk = (int)cdiv(j.n, RS_THREADS * ITEMS);
     {
         ProfScope ps(j.prof, P_SORT_HIST, st);
-        k_sort_hist<SRC><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, j.flags);
+        k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, j.flags);
     }
     {
         ProfScope ps(j.prof, P_SORT_SCAN, st);
@@ -174,22 +198,31 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     }
     {
         ProfScope ps(j.prof, P_SORT_SCATTER, st);
-        k_sort_scatter<SRC><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, vin, j.offsets, j.num_bags, j.n, j.limit, shift, rb, nblk,
-                                                                  j.ghist, j.dtot, kout, vout);
+        k_sort_scatter<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, vin, j.offsets, j.num_bags, j.n, j.limit, shift, rb,
+                                                                         nblk, j.ghist, j.dtot, kout, vout);
     }
+}
+
+// Tiles of RS_ITEMS keys per thread keep the six launches of a two-pass sort short for a few hundred thousand keys;
+// with more than 512 digits per pass a tile of that size holds about one key per digit, and the wider tile halves the
+// per-tile digit tables that the scan and the scatter prologue walk.
+template <int SRC>
+static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
+                        int shift, int rb) {
+    if (rb > 9) launch_pass<SRC, RS_ITEMS_WIDE>(j, st, kin, vin, kout, vout, shift, rb);
+    else launch_pass<SRC, RS_ITEMS>(j, st, kin, vin, kout, vout, shift, rb);
 }
 
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
     const int passes = (j.bits + RS_MAX_BITS - 1) / RS_MAX_BITS;
     const int rb = (j.bits + passes - 1) / passes;
-    const int nblk = (int)cdiv(j.n, RS_TILE);
     const int32_t* kin = j.keys_in; const int32_t* vin = j.vals_in;
     int32_t* kout = j.keysA; int32_t* vout = j.valsA;
     for (int p = 0; p < passes; ++p) {
         const int shift = p * rb;
-        if (p > 0 || j.src == SORT_SRC_PAIRS) launch_pass<SORT_SRC_PAIRS>(j, st, kin, vin, kout, vout, shift, rb, nblk);
-        else if (j.src == SORT_SRC_SLOTS) launch_pass<SORT_SRC_SLOTS>(j, st, kin, vin, kout, vout, shift, rb, nblk);
-        else launch_pass<SORT_SRC_COUNTS>(j, st, kin, vin, kout, vout, shift, rb, nblk);
+        if (p > 0 || j.src == SORT_SRC_PAIRS) launch_pass<SORT_SRC_PAIRS>(j, st, kin, vin, kout, vout, shift, rb);
+        else if (j.src == SORT_SRC_SLOTS) launch_pass<SORT_SRC_SLOTS>(j, st, kin, vin, kout, vout, shift, rb);
+        else launch_pass<SORT_SRC_COUNTS>(j, st, kin, vin, kout, vout, shift, rb);
         kin = kout; vin = vout;
         if (kout == j.keysA) { kout = j.keysB; vout = j.valsB; } else { kout = j.keysA; vout = j.valsA; }
     }

@@ -73,6 +73,17 @@ def bench_static_module(args, w, torch, dev):
     print(json.dumps(res), flush=True)
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -256,6 +267,8 @@ def main():
     tot_ids = sum(s["n_ids"] for s in timed)
     hit_ratio = sum(s["n_hit_ids"] for s in timed) / max(1, tot_ids)
     uniq_hit_ratio = sum(s["n_hit_unique"] for s in timed) / max(1, sum(s["n_unique"] for s in timed))
+    warm_in = stats[:args.warmup]
+    warm_in_hit = sum(s["n_hit_ids"] for s in warm_in) / max(1, sum(s["n_ids"] for s in warm_in))
     value = tot_ids / elapsed
     ms_per_step = elapsed / args.steps * 1e3
     mean = {k: float(np.mean([s[k] for s in timed])) for k in ("n_ids", "n_unique", "n_miss", "n_evict")}
@@ -401,7 +414,8 @@ def main():
         S = done
         cpu_baseline = {"value": round(ids_done / t_cpu, 1), "unit": "ids/s", "cores": 1,
                         "kind": "oracle", "sample": f"first {S} batches of the same trace (prepare+fwd+bwd, warm start), {t_cpu:.1f} s of CPU time",
-                        "host_cores_available": os.cpu_count(), "gpu_stats_identical_on_sample": bool(same)}
+                        "host_cores_available": os.cpu_count(), "cpu_model": cpu_model(),
+                        "gpu_stats_identical_on_sample": bool(same)}
         log(f"[bench] oracle: {cpu_baseline['value'] / 1e6:.2f} M ids/s on 1 core over {S} batches; stats identical: {same}")
         orc.close()
 
@@ -424,6 +438,7 @@ def main():
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
         "ids_from_host": bool(args.ids_from_host),
         "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5),
+        "warm_in": {"batches": args.warmup, "hit_ratio": round(warm_in_hit, 5), "timed": False},
         "roofline": roofline, "host_link": host_link, "kernels": kernels, "cpu_baseline": cpu_baseline,
     }
     cache.close()

@@ -16,10 +16,10 @@ constexpr int RT_THREADS = 256;
 constexpr int RT_WORDS = RT_THREADS * 4;
 // Radix sort of (slot, bag) pairs for the backward pass.
 constexpr int RS_THREADS = 256;
-constexpr int RS_ITEMS = 8;                      // keys per thread; RS_ITEMS_WIDE when a pass has more than 512 digits
-constexpr int RS_ITEMS_WIDE = 16;
-constexpr int RS_TILE = RS_THREADS * RS_ITEMS;    // the smaller tile: sizes the per-tile digit tables
-constexpr int RS_MAX_BITS = 11;
+constexpr int RS_ITEMS = 8;                      // keys per thread
+constexpr int RS_TILE = RS_THREADS * RS_ITEMS;
+constexpr int RS_TWO_PASS_BITS = 9;               // keys of up to 18 bits are sorted in two passes
+constexpr int RS_MAX_BITS = RS_TWO_PASS_BITS;     // most bits per pass: sizes the digit tables
 // Consecutive sorted lookups reduced by one row-group in the backward pass.
 #ifndef FC_BWD_CHUNK
 #define FC_BWD_CHUNK 32

@@ -1,4 +1,4 @@
-// Stable LSD radix sort of (key, value) int32 pairs, 64-wide wavefronts, up to 11 bits per pass.
+// Stable LSD radix sort of (key, value) int32 pairs, 64-wide wavefronts, up to 9 bits per pass.
 // Used by the backward pass (sort lookups by slot, value = bag) and by the static-module build
 // (sort ids by descending count).  Keys come from one of three sources, see SortSrc.
 #include "fc_internal.h"
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
 }
 
 
-template <int SRC, int ITEMS>
+template <int SRC, int ITEMS = RS_ITEMS>
 static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
                         int shift, int rb) {
     const int radix = 1 << rb;
@@ -203,18 +203,10 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     }
 }
 
-// Tiles of RS_ITEMS keys per thread keep the six launches of a two-pass sort short for a few hundred thousand keys;
-// with more than 512 digits per pass a tile of that size holds about one key per digit, and the wider tile halves the
-// per-tile digit tables that the scan and the scatter prologue walk.
-template <int SRC>
-static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
-                        int shift, int rb) {
-    if (rb > 9) launch_pass<SRC, RS_ITEMS_WIDE>(j, st, kin, vin, kout, vout, shift, rb);
-    else launch_pass<SRC, RS_ITEMS>(j, st, kin, vin, kout, vout, shift, rb);
-}
-
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
-    const int passes = (j.bits + RS_MAX_BITS - 1) / RS_MAX_BITS;
+    // Two passes up to 18 key bits (six launches, each bound by latency rather than by bytes); beyond that a tile of
+    // 2048 keys would hold about one key per digit and the per-tile digit tables dominate, so passes of at most 8 bits.
+    const int passes = j.bits <= 2 * RS_TWO_PASS_BITS ? (j.bits + RS_TWO_PASS_BITS - 1) / RS_TWO_PASS_BITS : (j.bits + 7) / 8;
     const int rb = (j.bits + passes - 1) / passes;
     const int32_t* kin = j.keys_in; const int32_t* vin = j.vals_in;
     int32_t* kout = j.keysA; int32_t* vout = j.valsA;

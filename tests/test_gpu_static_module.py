@@ -47,9 +47,9 @@ def test_freq_rank_edge_cases(torch_cuda):
     rng = np.random.default_rng(0)
     # no ids at all: every count is 0 -> identity ranking
     build_both(torch, 1000, [])
-    # one id only, many times (one 11-bit pass is not enough for the count); ragged tile sizes
+    # one id only, many times (one 9-bit pass is not enough for the count); ragged tile sizes
     build_both(torch, 4097, [np.full(5000, 17), np.full(3, 4096)])
-    # counts above 2^11 and 2^22 force two and three radix passes
+    # a count above 2^18 (5,000,000 needs 23 bits) takes three radix passes, the counts before one and two
     build_both(torch, 300, [np.concatenate([np.full(5_000_000, 7), rng.integers(0, 300, size=100_000)])])
     # a table larger than one sort tile with all-distinct counts
     ids = np.repeat(np.arange(3000), np.arange(3000) % 7 + 1)

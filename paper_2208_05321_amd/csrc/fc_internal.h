@@ -175,8 +175,9 @@ struct fc_cache {
     hipEvent_t ev_d2h[fc::DMA_BLOCKS] = {};
     hipEvent_t pf_dep = nullptr;                  // what the next early fetch of missing rows has to wait for
     // The early fetch (zero-copy reads) and the evicted-row block copy (DMA writes) share the host link all the time in
-    // the pipelined schedule; how they split it depends on the fetch's workgroup count, and a step is worst when the
-    // block copy is the slower one (the host then waits for block buffers).  Unless FC_FILL_BLOCKS_EARLY pins it, that
+    // the pipelined schedule; how they split it depends on the fetch's workgroup count, and a step gets longer, not
+    // shorter, once the block copy is the slower one (more fetch workgroups also slow the index kernels of the batch
+    // after next, which the following fetch waits for).  Unless FC_FILL_BLOCKS_EARLY pins it, that
     // count follows the measured durations: timing events around both, a smoothed ratio fetch / copy, one workgroup
     // fewer every few steps while the copy is the slower one, one more (up to the default, which suits steps that are
     // not bound by the link) while the fetch is clearly the slower one.

@@ -35,13 +35,23 @@ void prof_collect(fc_cache* c) {
     (void)hipStreamSynchronize(c->side);
     if (c->aux) (void)hipStreamSynchronize(c->aux);
     if (c->pre) (void)hipStreamSynchronize(c->pre);
+    // FC_TIMELINE=<file>: besides the totals, every span's start and end in us since the first span of this collection,
+    // one "name start end" line each (which kernels really run side by side, and what waits for what)
+    static FILE* timeline = getenv("FC_TIMELINE") ? fopen(getenv("FC_TIMELINE"), "w") : nullptr;
+    if (timeline && !c->spans.empty()) fprintf(timeline, "# %zu spans\n", c->spans.size());
     for (const ProfSpan& sp : c->spans) {
         float ms = 0.f;
+        if (timeline) {
+            float t0 = 0.f, t1 = 0.f;
+            if (hipEventElapsedTime(&t0, c->spans.front().a, sp.a) == hipSuccess && hipEventElapsedTime(&t1, c->spans.front().a, sp.b) == hipSuccess)
+                fprintf(timeline, "%s %.1f %.1f\n", kProfNames[sp.item], t0 * 1e3f, t1 * 1e3f);
+        }
         if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) { c->prof_ms[sp.item] += ms; c->prof_n[sp.item] += 1; }
         c->ev_pool.push_back(sp.a);
         c->ev_pool.push_back(sp.b);
     }
     c->spans.clear();
+    if (timeline) fflush(timeline);
 }
 
 // ---- state initialisation ----

@@ -125,7 +125,7 @@ enum {
  *   FC_MARK_IPT           ids per thread of the marking kernel (2)
  *   FC_TUNE_REPORT        if set, cache_destroy prints where the early-fetch workgroup count settled
  *   FC_TIMELINE           file that receives, whenever profiling totals are collected, one line "name start_us end_us"
- *                         per timed kernel or copy (read when profiling is first collected, not here) */
+ *                         per timed kernel or copy (read at every collection, not here) */
 int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_t* freq_rank_host,
                  float* host_weight, int64_t staging_rows, int32_t flags, void* hip_stream, fc_cache** out);
 

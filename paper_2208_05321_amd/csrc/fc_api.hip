@@ -7,6 +7,7 @@
 #include <new>
 #include <stdlib.h>
 #include <string.h>
+#include <string>
 #include <vector>
 
 namespace fc {
@@ -37,7 +38,11 @@ void prof_collect(fc_cache* c) {
     if (c->pre) (void)hipStreamSynchronize(c->pre);
     // FC_TIMELINE=<file>: besides the totals, every span's start and end in us since the first span of this collection,
     // one "name start end" line each (which kernels really run side by side, and what waits for what)
-    static FILE* timeline = getenv("FC_TIMELINE") ? fopen(getenv("FC_TIMELINE"), "w") : nullptr;
+    static FILE* timeline = nullptr;
+    static std::string timeline_path;
+    const char* want = getenv("FC_TIMELINE");
+    if (timeline && (!want || timeline_path != want)) { fclose(timeline); timeline = nullptr; }
+    if (!timeline && want && *want) { timeline = fopen(want, "w"); timeline_path = want; }
     if (timeline && !c->spans.empty()) fprintf(timeline, "# %zu spans\n", c->spans.size());
     for (const ProfSpan& sp : c->spans) {
         float ms = 0.f;

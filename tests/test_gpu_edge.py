@@ -366,3 +366,40 @@ def test_two_tables_interleaved(torch_cuda):
         g.check(); g.flush(); o.flush()
         assert_close(g.host_weight(), o.host, "host table")
         g.close()
+
+
+def test_profile_timeline_file(torch_cuda, tmp_path, monkeypatch):
+    """FC_TIMELINE: every timed kernel of the profiled steps appears once with start <= end, and the per-kernel totals of
+    cache_profile_get are the sums of those spans."""
+    torch = torch_cuda
+    from paper_2208_05321_amd import FreqCache
+    from paper_2208_05321_amd.timeline import load_first_collection
+    w = make_workload("c1")
+    dev = torch.device("cuda:0")
+    path = tmp_path / "timeline.txt"
+    monkeypatch.setenv("FC_TIMELINE", str(path))
+    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, dma_evict=True)
+    w.host_table(out=gpu.host_weight())
+    gpu.warm()
+    gpu.profile(True)
+    steps = 3
+    for t in range(steps):
+        ids, off = w.batch(t)
+        ids_d, off_d = torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev)
+        slots = gpu.prepare(ids_d, off_d)
+        gpu.embedding_bag_fwd(slots, off_d)
+        gpu.embedding_bag_bwd_sgd(slots, off_d, torch.from_numpy(w.grad(t, len(off) - 1)).to(dev), w.lr)
+    rep = gpu.profile_report()
+    gpu.profile(False)
+    monkeypatch.delenv("FC_TIMELINE")
+    gpu.profile(False)                                   # a collection without the variable closes the file
+    gpu.close()
+    spans = load_first_collection(str(path))
+    assert spans and all(a <= b for a, b, _ in spans)
+    for name in ("remap_mark", "bag_fwd", "bwd_reduce"):
+        mine = [(a, b) for a, b, n in spans if n == name]
+        assert len(mine) == steps == rep[name]["launches"]
+        assert abs(sum(b - a for a, b in mine) * 1e-3 - rep[name]["ms"]) < 0.01 * steps
+    fwd = sorted(a for a, b, n in spans if n == "bag_fwd")
+    bwd = sorted(a for a, b, n in spans if n == "bwd_reduce")
+    assert all(f < g for f, g in zip(fwd, bwd))           # same stream: forward before backward in every step

@@ -57,7 +57,7 @@ def bench_static_module(args, w, torch, dev):
     ok = bool(np.array_equal(cnt, counts_o) and np.array_equal(fr, fr_o))
     # algorithmic bytes of the build: max scan + per radix pass (read key, read pair, write pair) + rank scatter + copies out
     bits = max(1, int(cnt.max()).bit_length())
-    passes = -(-bits // 11)
+    passes = -(-bits // 9) if bits <= 18 else -(-bits // 8)      # the library's rule: two passes up to 18 key bits
     build_bytes = w.num_rows * (4 + passes * (4 + 8 + 8) + 8 + 12)
     res = {"metric": "static module on the GPU: ids counted per second; rows ranked per second",
            "value": round(n_ids / t_count, 1), "unit": "ids/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -332,13 +332,6 @@ def main():
         # candidates: the kernels that stream rows through HBM; the index kernels are bound by latency, and beside a
         # copy kernel (as under a tracer) they can wait longer than any of these run
         hbm_kernels = [k for k in ("bag_fwd", "bwd_reduce", "evict_gather", "rows_in") if k in kernels and "alg_GBps" in kernels[k]]
-        dom = max(hbm_kernels, key=lambda k: kernels[k]["us_per_step"])
-        ach = kernels[dom]["alg_GBps"]
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4),
-                    "traffic": PMC_TRAFFIC_C2.get(dom) if (w.name == "c2" and args.scale == 1.0 and args.cache_ratio == 0.015) else None,
-                    "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"],
-                    "measured": "HIP events around every launch, in the timed schedule (%s)" % args.schedule}
         if pipelined:
             # In the pipelined schedule this kernel shares compute units with the host-link row fetch of the next batch
             # (its waves wait on host reads).  Two more measurements of the same kernels on the same data:
@@ -364,16 +357,29 @@ def main():
             for name in ("bag_fwd", "bwd_reduce", "bwd_fixup"):
                 if name in rep_alone and name in kernels:
                     kernels[name]["alone_avg_us"] = round(rep_alone[name]["ms"] / rep_alone[name]["launches"] * 1e3, 2)
-            if "alone_avg_us" in kernels[dom]:
-                gbs = kernels[dom]["alg_bytes_per_launch"] / (kernels[dom]["alone_avg_us"] * 1e-6) / 1e9
-                roofline["alone"] = {"avg_us": kernels[dom]["alone_avg_us"], "achieved": round(gbs, 1),
-                                     "frac": round(gbs / HBM_PEAK_GBS, 4),
-                                     "measured": "HIP events, the kernel relaunched on the last batch with nothing else running"}
-            if "serial_avg_us" in kernels[dom]:
-                gbs = kernels[dom]["alg_bytes_per_launch"] / (kernels[dom]["serial_avg_us"] * 1e-6) / 1e9
-                roofline["serial"] = {"avg_us": kernels[dom]["serial_avg_us"], "achieved": round(gbs, 1),
-                                      "frac": round(gbs / HBM_PEAK_GBS, 4),
-                                      "measured": "HIP events, plain schedule (only the DMA copy of the evicted block beside it)"}
+        # the one that takes longest per step; in the pipelined schedule judged by the plain-schedule pass, where the
+        # times do not depend on what the other streams happen to run beside it (forward and backward are close, and
+        # which of the two waits longer for a compute unit changes from run to run)
+        dom = max(hbm_kernels, key=lambda k: kernels[k].get("serial_avg_us", kernels[k]["avg_us"]) * kernels[k]["launches_per_step"])
+        ach = kernels[dom]["alg_GBps"]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4),
+                    "traffic": PMC_TRAFFIC_C2.get(dom) if (w.name == "c2" and args.scale == 1.0 and args.cache_ratio == 0.015) else None,
+                    "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"],
+                    "measured": "HIP events around every launch, in the timed schedule (%s)" % args.schedule}
+        if "alone_avg_us" in kernels[dom]:
+            gbs = kernels[dom]["alg_bytes_per_launch"] / (kernels[dom]["alone_avg_us"] * 1e-6) / 1e9
+            roofline["alone"] = {"avg_us": kernels[dom]["alone_avg_us"], "achieved": round(gbs, 1),
+                                 "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                 "measured": "HIP events, the kernel relaunched on the last batch with nothing else running"}
+        if "serial_avg_us" in kernels[dom]:
+            gbs = kernels[dom]["alg_bytes_per_launch"] / (kernels[dom]["serial_avg_us"] * 1e-6) / 1e9
+            roofline["serial"] = {"avg_us": kernels[dom]["serial_avg_us"], "achieved": round(gbs, 1),
+                                  "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                  "measured": "HIP events, plain schedule (only the DMA copy of the evicted block beside it)"}
+        if any(r.get("frac", 0) > 1 for r in (roofline, roofline.get("alone", {}), roofline.get("serial", {}))):
+            roofline["note"] = ("algorithmic bytes count one row per lookup; rows looked up again and again are served by the "
+                                "caches, so the fraction of the HBM peak can exceed 1")
         link = {}
         for name, direction, rows in (("miss_fill", "h2d", m_m), ("evict_store", "d2h", e_m),
                                       ("h2d_block", "h2d", m_m), ("d2h_block", "d2h", e_m)):

@@ -406,7 +406,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) { (void)hipGetLastError(); return FC_ERR_HIP; }
     fc_cache* c = new (std::nothrow) fc_cache();
-    if (!c) return FC_ERR_INVALID_ARG;
+    if (!c) return FC_ERR_OOM_PINNED;                    // host memory
     const int rc = create(num_rows, dim, cache_rows, freq_rank_host, host_weight, staging_rows, flags, hip_stream, c);
     if (rc != FC_OK) { destroy(c); return rc; }
     *out = c;
@@ -443,16 +443,11 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
     if (c->last_pst != c->pre) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
     const int rc = prepare_impl(c, c->pre, true, ids_dev, n, offsets_dev, num_bags, slots_dev);
     c->pst = c->stream;
-    if (rc != FC_OK) {
-        // nothing changed; keep the streams ordered all the same
-        FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
-        c->last_pst = c->pre; c->next_pending = true;
-        return rc;
-    }
+    // also after a refusal (nothing changed then): the streams stay ordered all the same
     FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
     c->last_pst = c->pre;
     c->next_pending = true;
-    return FC_OK;
+    return rc;
 }
 
 int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,

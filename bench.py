@@ -20,9 +20,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch at config 2 from rocprofv3 --pmc (2 x FETCH_SIZE + WRITE_SIZE, scale factors from a plain copy;
-# profiles/c2_pmc_fetch_write_size.md); only quoted when the workload is exactly config 2.
-PMC_TRAFFIC_C2 = {"bwd_reduce": 313.6e6, "bag_fwd": 312.2e6}
+# HBM bytes per launch from rocprofv3 --pmc (2 x FETCH_SIZE + WRITE_SIZE, scale factors from a plain copy;
+# profiles/c2_pmc_fetch_write_size.md, profiles/c4_pmc_fetch_write_size.md); only quoted when the workload is exactly
+# the configuration the counters were collected on.
+PMC_TRAFFIC = {"c2": {"bwd_reduce": 313.6e6, "bag_fwd": 312.2e6},
+               "c4": {"bwd_reduce": 1085.2e6, "bag_fwd": 1158.3e6}}
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 LINK_PEAK_GBS = 64.0       # PCIe Gen5 x16, per direction, nominal
 
@@ -364,7 +366,7 @@ def main():
         ach = kernels[dom]["alg_GBps"]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(ach / HBM_PEAK_GBS, 4),
-                    "traffic": PMC_TRAFFIC_C2.get(dom) if (w.name == "c2" and args.scale == 1.0 and args.cache_ratio == 0.015) else None,
+                    "traffic": PMC_TRAFFIC.get(w.name, {}).get(dom) if (args.scale == 1.0 and args.cache_ratio == 0.015) else None,
                     "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"], "avg_us": kernels[dom]["avg_us"],
                     "measured": "HIP events around every launch, in the timed schedule (%s)" % args.schedule}
         if "alone_avg_us" in kernels[dom]:

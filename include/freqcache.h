@@ -129,6 +129,15 @@ enum {
 int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_t* freq_rank_host,
                  float* host_weight, int64_t staging_rows, int32_t flags, void* hip_stream, fc_cache** out);
 
+/* Allocate now everything the per-batch calls would otherwise allocate when they first meet a batch of that size:
+ * the per-id rank buffer of cache_prepare, the sort scratch and partial-sum rows of embedding_bag_bwd_sgd for batches
+ * of up to max_ids lookups (three sort sets of 16 * max_ids bytes), and, if pipelined != 0, the two arrival blocks of
+ * cache_plan_next (staging_rows * dim * 4 bytes each).  The transmitter's memory stays bounded by staging_rows
+ * (Section 4.3); this call only moves the allocations out of the training loop.  Optional: without it (or for a larger
+ * batch later) the buffers grow on demand, which costs a hipMalloc and a device-wide synchronisation in that step.
+ * Synchronous.  Errors: INVALID_ARG, OOM_DEVICE, HIP. */
+int cache_reserve(fc_cache* c, int64_t max_ids, int32_t pipelined);
+
 /* Cache warm-up (Section 4.3): empty the cache and load rows 0..cache_rows-1 of the host table into
  * slots 0..cache_rows-1.  cache_create(FC_WARM) calls this.  Synchronous.  Does not write back
  * resident rows first (call cache_flush if they carry updates). */

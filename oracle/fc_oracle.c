@@ -254,19 +254,25 @@ int fco_prepare_lookahead(fco* o, const int64_t* ids, int64_t n, const int64_t* 
 }
 
 /* EmbeddingBag, mode=sum, on the cached weight: out[b] = sum over the bag, in position order. */
-int fco_embedding_bag_fwd(const fco* o, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out) {
-    if (!o || !offsets || !out) return FCO_INVALID_ARG;
-    const int32_t D = o->D;
+/* The bag sum itself, on any weight array of `rows` rows: out[b] = rows of bag b added one by one in position order. */
+int fco_bag_sum(const float* weight, int64_t rows, int32_t D, const int32_t* slots, int64_t n, const int64_t* offsets,
+                int64_t num_bags, float* out) {
+    if (!weight || !offsets || !out) return FCO_INVALID_ARG;
     for (int64_t b = 0; b < num_bags; ++b) {
         float* ob = out + (size_t)b * D;
         for (int32_t c = 0; c < D; ++c) ob[c] = 0.0f;
         for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {
-            if (i >= n || slots[i] < 0 || slots[i] >= o->C) return FCO_INVALID_ARG;
-            const float* row = o->cache + (size_t)slots[i] * D;
+            if (i >= n || slots[i] < 0 || slots[i] >= rows) return FCO_INVALID_ARG;
+            const float* row = weight + (size_t)slots[i] * D;
             for (int32_t c = 0; c < D; ++c) ob[c] = ob[c] + row[c];
         }
     }
     return FCO_OK;
+}
+
+int fco_embedding_bag_fwd(const fco* o, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out) {
+    if (!o) return FCO_INVALID_ARG;
+    return fco_bag_sum(o->cache, o->C, o->D, slots, n, offsets, num_bags, out);
 }
 
 /* Backward of the sum-bag + SGD step: each lookup of a row receives its bag's output gradient;

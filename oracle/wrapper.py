@@ -47,6 +47,8 @@ def _load(path: str | None = None):
         L.fco_prepare_lookahead.restype = ctypes.c_int
         L.fco_embedding_bag_fwd.argtypes = [vp, vp, i64, vp, i64, vp]
         L.fco_embedding_bag_fwd.restype = ctypes.c_int
+        L.fco_bag_sum.argtypes = [vp, i64, i32, vp, i64, vp, i64, vp]
+        L.fco_bag_sum.restype = ctypes.c_int
         L.fco_embedding_bag_bwd_sgd.argtypes = [vp, vp, i64, vp, i64, vp, f32]
         L.fco_embedding_bag_bwd_sgd.restype = ctypes.c_int
         L.fco_flush.argtypes = [vp]
@@ -68,6 +70,21 @@ def _load(path: str | None = None):
 
 
 STAT_FIELDS = ("n_ids", "n_unique", "n_hit_unique", "n_hit_ids", "n_miss", "n_evict", "bytes_h2d", "bytes_d2h")
+
+
+def bag_sum(weight: np.ndarray, slots: np.ndarray, offsets: np.ndarray) -> np.ndarray:
+    """EmbeddingBag-sum of the rows `slots` of any fp32 weight array [rows, dim], position order, fp32
+    (the arithmetic of Oracle.embedding_bag_fwd, on rows the caller supplies)."""
+    L = _load()
+    weight = np.ascontiguousarray(weight, dtype=np.float32)
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    out = np.empty((offsets.shape[0] - 1, weight.shape[1]), dtype=np.float32)
+    rc = L.fco_bag_sum(weight.ctypes.data, weight.shape[0], weight.shape[1], slots.ctypes.data, slots.shape[0],
+                       offsets.ctypes.data, offsets.shape[0] - 1, out.ctypes.data)
+    if rc:
+        raise OracleError(rc)
+    return out
 
 
 class Oracle:

@@ -24,7 +24,7 @@ STAT_FIELDS = ("n_ids", "n_unique", "n_hit_unique", "n_hit_ids", "n_miss", "n_ev
 
 # every symbol include/freqcache.h declares
 EXPORTS = (
-    "cache_create", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_plan_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
+    "cache_create", "cache_reserve", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_plan_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
     "cache_check", "cache_destroy", "cache_last_stats", "cache_copy_state", "cache_last_lists", "cache_copy_rows",
     "cache_host_weight", "cache_strerror", "cache_profile_enable", "cache_profile_count", "cache_profile_name",
     "cache_profile_get", "freq_create", "freq_add", "freq_build", "freq_destroy", "table_reorder",
@@ -56,6 +56,7 @@ def load_library(path: str | None = None):
     L = ctypes.CDLL(p)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     L.cache_create.argtypes = [i64, i32, i64, vp, vp, i64, i32, vp, ctypes.POINTER(vp)]
+    L.cache_reserve.argtypes = [vp, i64, i32]
     L.cache_warm.argtypes = [vp]
     L.cache_prepare.argtypes = [vp, vp, i64, vp, i64, vp]
     L.cache_prepare_next.argtypes = [vp, vp, i64, vp, i64, vp]
@@ -150,6 +151,9 @@ class FreqCache:
         p = self._L.cache_host_weight(self._h)
         buf = (ctypes.c_float * (self.num_rows * self.dim)).from_address(p)
         return np.frombuffer(buf, dtype=np.float32).reshape(self.num_rows, self.dim)
+
+    def reserve(self, max_ids: int, pipelined: bool = False):
+        self._check(self._L.cache_reserve(self._h, int(max_ids), int(bool(pipelined))), "cache_reserve")
 
     def warm(self):
         self._check(self._L.cache_warm(self._h), "cache_warm")

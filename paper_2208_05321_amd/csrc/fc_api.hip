@@ -344,13 +344,20 @@ static void tune_fetch_grid(fc_cache* c, int k) {
     else if (c->tune_ratio > 1.06f && c->fill_blocks_early < c->fill_blocks_early_max) ++c->fill_blocks_early;
 }
 
+// the arrival block of list set k (cache_plan_next fetches missing rows into it ahead of time)
+static bool ensure_arrival_block(fc_cache* c, int k) {
+    if (c->arrive[k]) return true;
+    if (hipMalloc((void**)&c->arrive[k], (size_t)c->staging_rows * c->D * 4) != hipSuccess) {
+        (void)hipGetLastError(); c->arrive[k] = nullptr;
+        return false;
+    }
+    return true;
+}
+
 // cache_plan_next: the planned batch's missing rows into the arrival block of its list set, on the stream pf
 static int fetch_early(fc_cache* c, int64_t M) {
     const int k = c->lset;
-    if (!c->arrive[k] && hipMalloc((void**)&c->arrive[k], (size_t)c->staging_rows * c->D * 4) != hipSuccess) {
-        (void)hipGetLastError(); c->arrive[k] = nullptr;
-        return FC_OK;                  // no room for the block: the rows are fetched at cache_advance instead
-    }
+    if (!ensure_arrival_block(c, k)) return FC_OK;   // no room for the block: the rows are fetched at cache_advance instead
     if (c->tune_early) tune_fetch_grid(c, k);
     FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
     if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
@@ -379,6 +386,7 @@ static int adopt_next(fc_cache* c) {
         c->next_pending = false;
         c->last_pst = c->stream;
     }
+    c->cur_ticket = c->pending_ticket;     // the batch prepared ahead of time (if any) is the current one now
     return FC_OK;
 }
 
@@ -413,6 +421,17 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     return FC_OK;
 }
 
+int cache_reserve(fc_cache* c, int64_t max_ids, int32_t pipelined) {
+    const int64_t LIM = ((int64_t)1 << 31) - 65536;
+    if (!c || max_ids < 0 || max_ids >= LIM) return FC_ERR_INVALID_ARG;
+    FC_HIP(hipSetDevice(c->device));
+    FC_TRY(ensure_rbuf(c, max_ids));
+    FC_TRY(reserve_bwd(c, max_ids));
+    if (pipelined && !(c->flags & FC_TRANSMIT_STAGED))
+        for (int k = 0; k < 2; ++k) if (!ensure_arrival_block(c, k)) return FC_ERR_OOM_DEVICE;
+    return FC_OK;
+}
+
 int cache_warm(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
@@ -429,7 +448,9 @@ int cache_prepare(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t*
     FC_HIP(hipSetDevice(c->device));
     FC_HIP(hipEventRecord(c->ev_s_now, c->stream));
     FC_TRY(adopt_next(c));
-    return prepare_impl(c, c->stream, false, ids_dev, n, offsets_dev, num_bags, slots_dev);
+    const int rc = prepare_impl(c, c->stream, false, ids_dev, n, offsets_dev, num_bags, slots_dev);
+    if (rc == FC_OK) c->cur_ticket = c->pending_ticket = c->ticket;
+    return rc;
 }
 
 int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_t* offsets_dev, int64_t num_bags,
@@ -447,6 +468,7 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
     FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
     c->last_pst = c->pre;
     c->next_pending = true;
+    if (rc == FC_OK) c->pending_ticket = c->ticket;
     return rc;
 }
 
@@ -469,6 +491,7 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
         return rc;
     }
     c->planned = mv;
+    c->pending_ticket = c->ticket;
     int rc2 = FC_OK;
     // Missing rows ahead of time: they are not resident, so nothing the caller's stream still does to the current
     // batch changes them; their newest copy is in the host table or in an evicted-row block (transit marks), and the
@@ -489,6 +512,7 @@ int cache_advance(fc_cache* c) {
         FC_HIP(hipStreamWaitEvent(c->stream, c->ev_pre_done, 0));
         c->next_pending = false;
     }
+    c->cur_ticket = c->pending_ticket;
     return FC_OK;
 }
 

@@ -339,6 +339,17 @@ static int ensure_sort(SortBufs& sb, int64_t n) {
     return FC_OK;
 }
 
+static int ensure_part(fc_cache* c, int64_t groups);
+static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int64_t* rblocks, size_t* lds);
+
+int reserve_bwd(fc_cache* c, int64_t n) {
+    if (n <= 0) return FC_OK;
+    for (SortBufs& sb : c->sb) FC_TRY(ensure_sort(sb, n));
+    int rthreads; int64_t rblocks; size_t lds;
+    bwd_geometry(c, n, &rthreads, &rblocks, &lds);
+    return ensure_part(c, rblocks);
+}
+
 static int ensure_part(fc_cache* c, int64_t groups) {
     if (groups > c->part_groups) {
         FC_HIP(hipDeviceSynchronize());
@@ -382,6 +393,9 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     c->rec_next ^= 1;
     PresortRec& r = c->rec[k];
     r.valid = false;
+    // the other record stays only if it belongs to the current batch (look-ahead / pipelined schedules: its backward pass
+    // may still be to come); a batch that was prepared and never trained on leaves nothing behind
+    if (c->rec[k ^ 1].valid && c->rec[k ^ 1].ticket != c->cur_ticket) c->rec[k ^ 1].valid = false;
     if (!c->presort || n <= 0 || num_bags <= 0) return FC_OK;
     FC_TRY(ensure_sort(c->sb[k], n));
     FC_HIP(hipEventRecord(c->ev_slots, c->pst));
@@ -391,6 +405,7 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     FC_TRY(sort_pairs(c, c->sb[k], c->aux, slots, n, offsets, num_bags, &r.keys, &r.vals));
     FC_HIP(hipEventRecord(r.ev_sorted, c->aux));
     r.slots = slots; r.n = n; r.offsets = offsets; r.bags = num_bags;
+    r.ticket = c->ticket;
     r.valid = true;
     return FC_OK;
 }
@@ -408,7 +423,8 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     FC_TRY(ensure_part(c, rblocks));
     const int32_t* kin = nullptr; const int32_t* vin = nullptr;
     for (PresortRec& r : c->rec) {
-        if (r.valid && r.slots == slots && r.n == n && r.offsets == offsets && r.bags == num_bags) {
+        // sorted ahead of time by the call that prepared the current batch, from these very buffers
+        if (r.valid && r.ticket == c->cur_ticket && r.slots == slots && r.n == n && r.offsets == offsets && r.bags == num_bags) {
             FC_HIP(hipStreamWaitEvent(st, r.ev_sorted, 0));      // sorted ahead of time
             kin = r.keys; vin = r.vals;
             r.valid = false;

@@ -73,6 +73,7 @@ constexpr int DMA_BLOCKS = FC_DMA_BLOCKS;
 struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0, transit_base = -1; bool arrived = false; };
 struct PresortRec {
     bool valid = false;
+    int32_t ticket = 0;                 // number of the cache_prepare / _next / plan_next call whose slots it sorted
     const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
     int64_t n = 0, bags = 0;
     const int32_t *keys = nullptr, *vals = nullptr;
@@ -208,6 +209,10 @@ struct fc_cache {
     hipEvent_t ev_slots = nullptr;
     fc::PresortRec rec[2];
     int rec_next = 0;
+    // A record serves the backward pass of the batch it was made for and no other: cur_ticket = the call that prepared
+    // the current batch (the one forward / backward run on), pending_ticket = the call that prepared the batch
+    // cache_advance will make current.
+    int32_t cur_ticket = 0, pending_ticket = 0;
 
     // last prepare
     fc_stats last = {};
@@ -265,6 +270,8 @@ int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
 int dma_quiesce(fc_cache* c, hipStream_t st);
 int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags);
+int ensure_rbuf(fc_cache* c, int64_t n);  // per-id rank buffer for batches of n ids
+int reserve_bwd(fc_cache* c, int64_t n);   // sort scratch of all three sets and the partial rows for batches of n lookups
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
              const float* grad, float lr);
 

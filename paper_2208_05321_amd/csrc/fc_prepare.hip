@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void k_slots_out(const int32_t* __restrict__ r
 }
 
 // ---------------------------------------------------------------------------------------------------------
-static int ensure_rbuf(fc_cache* c, int64_t n) {
+int ensure_rbuf(fc_cache* c, int64_t n) {
     if (n <= c->n_cap) return FC_OK;
     FC_HIP(hipDeviceSynchronize());
     if (c->rbuf) FC_HIP(hipFree(c->rbuf));

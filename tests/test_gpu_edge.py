@@ -403,3 +403,42 @@ def test_profile_timeline_file(torch_cuda, tmp_path, monkeypatch):
     fwd = sorted(a for a, b, n in spans if n == "bag_fwd")
     bwd = sorted(a for a, b, n in spans if n == "bwd_reduce")
     assert all(f < g for f, g in zip(fwd, bwd))           # same stream: forward before backward in every step
+
+
+@pytest.mark.parametrize("dma", [False, True])
+def test_batch_prepared_but_not_trained_leaves_no_sort_behind(torch_cuda, dma):
+    """Static input / slot buffers reused by every batch (as a training loop with preallocated tensors does), and
+    batches that are prepared and pooled but never trained on (evaluation steps): the backward pass of a later batch
+    must use that batch's own sorted lookups, never the ones sorted ahead of time for an earlier batch that happened to
+    live in the same buffers.  Also with reserved buffers (cache_reserve), so that nothing is allocated in the loop."""
+    torch = torch_cuda
+    w = make_workload("c2", scale=0.05, cache_ratio=0.03)
+    gpu, orc = make_pair(w, warm=True, dma_evict=dma)
+    dev = torch.device("cuda:0")
+    n = len(w.batch(0)[0])
+    gpu.reserve(n, pipelined=True)
+    ids_d = torch.empty(n, dtype=torch.int64, device=dev)
+    off_d = torch.empty(w.bags_per_batch + 1, dtype=torch.int64, device=dev)
+    slots_d = torch.empty(n, dtype=torch.int32, device=dev)
+    grad_d = torch.empty((w.bags_per_batch, w.dim), dtype=torch.float32, device=dev)
+    for t in range(9):
+        ids, off = w.batch(t)
+        assert len(ids) == n
+        torch.cuda.synchronize()
+        ids_d.copy_(torch.from_numpy(ids)); off_d.copy_(torch.from_numpy(off))
+        so = orc.prepare(ids, off)
+        gpu.prepare(ids_d, off_d, out=slots_d)
+        assert np.array_equal(slots_d.cpu().numpy(), so), f"batch {t}: slots"
+        out = gpu.embedding_bag_fwd(slots_d, off_d)
+        assert_close(out.cpu().numpy(), orc.embedding_bag_fwd(so, off), f"batch {t}: pooled output")
+        if t % 3 != 1:                          # batches 1, 4, 7 are evaluation steps: no backward pass
+            g = w.grad(t, w.bags_per_batch)
+            grad_d.copy_(torch.from_numpy(g))
+            gpu.embedding_bag_bwd_sgd(slots_d, off_d, grad_d, w.lr)
+            orc.embedding_bag_bwd_sgd(so, off, g, w.lr)
+        assert_close(gpu.rows(), orc.cache, f"batch {t}: cached rows")
+    gpu.check()
+    gpu.flush()
+    orc.flush()
+    assert_close(gpu.host_weight(), orc.host, "host table")
+    gpu.close()

@@ -28,7 +28,7 @@ def torch_cuda():
 def test_config1_full(torch_cuda, warm):
     log(f"config 1, warm={warm}")
     w = make_workload("c1")
-    tot = run_parity(w, w.num_batches, warm=warm)
+    tot = run_parity(w, w.num_batches, warm=warm, exact_values=True)    # all-ones gradients: every sum is exact
     assert 0.5 < tot["hit_ids"] / tot["ids"] < 0.95
 
 

@@ -133,8 +133,8 @@ MUTANTS = [
     ("missed row not loaded", "memcpy(o->cache + (size_t)s * D, o->host + (size_t)k * D, (size_t)D * 4);\n            o->slot_rank[s] = k;",
      "o->slot_rank[s] = k;"),
     ("hit count per unique row", "for (int64_t i = 0; i < n; ++i) if (o->rank_slot[r[i]] >= 0) ++hit_ids;", "hit_ids = nH;"),
-    ("forward drops the last lookup of a bag", "for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {\n            if (i >= n || slots[i] < 0 || slots[i] >= o->C) return FCO_INVALID_ARG;\n            const float* row",
-     "for (int64_t i = offsets[b]; i < offsets[b + 1] - 1; ++i) {\n            if (i >= n || slots[i] < 0 || slots[i] >= o->C) return FCO_INVALID_ARG;\n            const float* row"),
+    ("forward drops the last lookup of a bag", "for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {\n            if (i >= n || slots[i] < 0 || slots[i] >= rows) return FCO_INVALID_ARG;\n            const float* row",
+     "for (int64_t i = offsets[b]; i < offsets[b + 1] - 1; ++i) {\n            if (i >= n || slots[i] < 0 || slots[i] >= rows) return FCO_INVALID_ARG;\n            const float* row"),
     ("SGD step with the wrong sign", "row[c] = row[c] - step;", "row[c] = row[c] + step;"),
     ("gradient of the wrong bag", "const float* gb = grad_out + (size_t)b * D;", "const float* gb = grad_out + (size_t)(b > 0 ? b - 1 : 0) * D;"),
     ("warm-up in reverse order", "o->slot_rank[s] = (int32_t)s;\n            o->rank_slot[s] = (int32_t)s;\n            memcpy(o->cache + (size_t)s * D, host + (size_t)s * D, (size_t)D * 4);",

@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the cache step + EmbeddingBag forward/backward on one MI355X.
 
-A step = cache_prepare + embedding_bag_fwd + embedding_bag_bwd_sgd on one batch of synthetic ids
-(config 2 by default: 26 features in one 10M x 128 fp32 table, batch 16,384 x 26 one-hot ids, cache 1.5%).
-Prints ONE JSON line.  The byte model behind `roofline` (what one launch of each kernel has to move) is the `model`
+A step = cache_prepare + embedding_bag_fwd + embedding_bag_bwd_sgd on one batch of synthetic ids.  Default workload:
+config 4, the largest configuration that fits one GPU (26 features in one 100M x 128 fp32 table of 51.2 GB in pinned
+host memory, batch 65,536 x 26 one-hot ids, cache 1.5%, hot set rotating every 100 batches); `--config c2` etc. select
+the others.  Prints ONE JSON line.  The byte model behind `roofline` (what one launch of each kernel has to move) is the `model`
 table in profile_pass below.
 """
 from __future__ import annotations
@@ -89,9 +90,9 @@ def cpu_model() -> str:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c4")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--cache-ratio", type=float, default=0.015)
     ap.add_argument("--transmitter", choices=("dma", "direct", "staged"), default="dma",
@@ -165,6 +166,7 @@ def main():
     slots = torch.empty(max_n, dtype=torch.int32, device=dev)
     out = torch.empty((nb, w.dim), dtype=torch.float32, device=dev)
     log(f"[bench] {total_steps + 2 * P + 1} batches on device ({time.time() - t0:.1f}s)")
+    cache.reserve(max_n, pipelined=True)          # nothing is allocated inside the loop
 
     if args.calib_copy_mb > 0:
         a = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device=dev)
@@ -259,20 +261,34 @@ def main():
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
+    cache.check()                        # nothing of the warm-up is still on its way (host scatter threads included)
     t_start = time.perf_counter()
     for t in range(args.warmup, total_steps):
         step(t)
     torch.cuda.synchronize()
+    cache.check()                        # the clock stops once every evicted row of the timed steps is in the host table
     elapsed = time.perf_counter() - t_start
-    cache.check()
-    timed = stats[args.warmup:]
-    tot_ids = sum(s["n_ids"] for s in timed)
+    # one entry per prepared batch; the pipelined schedules have prepared one batch beyond the last timed step
+    timed = stats[args.warmup:total_steps]
+    assert len(timed) == args.steps
+    tot_ids = sum(n_ids[args.warmup:total_steps])
     hit_ratio = sum(s["n_hit_ids"] for s in timed) / max(1, tot_ids)
     uniq_hit_ratio = sum(s["n_hit_unique"] for s in timed) / max(1, sum(s["n_unique"] for s in timed))
     warm_in = stats[:args.warmup]
     warm_in_hit = sum(s["n_hit_ids"] for s in warm_in) / max(1, sum(s["n_ids"] for s in warm_in))
     value = tot_ids / elapsed
     ms_per_step = elapsed / args.steps * 1e3
+    # workloads whose hot set moves (config 4): hit ratio of the timed steps before and after every rotation they cross
+    phases = None
+    if w.drift_every:
+        phases = []
+        for ph in sorted({t // w.drift_every for t in range(args.warmup, total_steps)}):
+            sel = [stats[t] for t in range(args.warmup, total_steps) if t // w.drift_every == ph]
+            phases.append({"batches": [ph * w.drift_every if ph * w.drift_every > args.warmup else args.warmup,
+                                       min((ph + 1) * w.drift_every, total_steps) - 1],
+                           "rotations_so_far": ph,
+                           "hit_ratio": round(sum(x["n_hit_ids"] for x in sel) / max(1, sum(x["n_ids"] for x in sel)), 5),
+                           "miss_per_step": round(float(np.mean([x["n_miss"] for x in sel])), 1)})
     mean = {k: float(np.mean([s[k] for s in timed])) for k in ("n_ids", "n_unique", "n_miss", "n_evict")}
     log(f"[bench] {args.steps} steps in {elapsed:.4f}s: {value / 1e6:.1f} M ids/s, {ms_per_step:.3f} ms/step, "
         f"hit ratio {hit_ratio:.4f}, per batch unique {mean['n_unique']:.0f} miss {mean['n_miss']:.0f}")
@@ -309,12 +325,12 @@ def main():
                 "miss_fill": m_m * (2 * R + 8),
                 "rows_in": m_m * (2 * R + 4),
                 "slots_out": n_m * 12,
-                "bag_fwd": n_m * (R + 4) + nb * (R + 8),
-                "bwd_reduce": n_m * 8 + nb * R + 2 * u_m * R,                  # grad read once per bag (one-hot: per id)
+                # forward: every DISTINCT row once (a row looked up again is served by the caches), slots, offsets, outputs
+                "bag_fwd": u_m * R + n_m * 4 + nb * (R + 8),
+                # backward: sorted pairs, every gradient row once, every distinct row read and written
+                "bwd_reduce": n_m * 8 + nb * R + 2 * u_m * R,
                 "sort_hist": n_m * 4, "sort_scatter": n_m * 16,
             }
-            if w.multi_hot:
-                model["bwd_reduce"] = n_m * 8 + n_m * R + 2 * u_m * R        # every lookup reads its bag's gradient row
             ks = {}
             for name, r in rep.items():
                 avg_us = r["ms"] / r["launches"] * 1e3
@@ -326,9 +342,10 @@ def main():
                     k["alg_bytes_per_launch"] = int(per_launch)
                     k["alg_GBps"] = round(per_launch / (avg_us * 1e-6) / 1e9, 1)
                 ks[name] = k
-            return ks, m_m, e_m
+            step_bytes = sum(model[name] for name in model if name in ks)       # all launches of a step together
+            return ks, m_m, e_m, step_bytes
 
-        kernels, m_m, e_m = profile_pass(step, total_steps)
+        kernels, m_m, e_m, step_bytes = profile_pass(step, total_steps)
         # HBM-bound kernels on the caller's stream (the sort runs on the auxiliary stream under the miss fill, where
         # its event-bracketed time says more about the fill than about the sort)
         # candidates: the kernels that stream rows through HBM; the index kernels are bound by latency, and beside a
@@ -340,7 +357,7 @@ def main():
             # "serial": a pass in the plain schedule (one stream; the DMA copy of the evicted block still runs beside the
             # forward / backward kernels), and "alone": forward and backward launched again and again on the last batch
             # with a device synchronisation in between, nothing else on the GPU.
-            serial, _, _ = profile_pass(step_plain, total_steps + P)
+            serial, _, _, _ = profile_pass(step_plain, total_steps + P)
             for name, k in serial.items():
                 if name in kernels:
                     kernels[name]["serial_avg_us"] = k["avg_us"]
@@ -359,10 +376,8 @@ def main():
             for name in ("bag_fwd", "bwd_reduce", "bwd_fixup"):
                 if name in rep_alone and name in kernels:
                     kernels[name]["alone_avg_us"] = round(rep_alone[name]["ms"] / rep_alone[name]["launches"] * 1e3, 2)
-        # the one that takes longest per step; in the pipelined schedule judged by the plain-schedule pass, where the
-        # times do not depend on what the other streams happen to run beside it (forward and backward are close, and
-        # which of the two waits longer for a compute unit changes from run to run)
-        dom = max(hbm_kernels, key=lambda k: kernels[k].get("serial_avg_us", kernels[k]["avg_us"]) * kernels[k]["launches_per_step"])
+        # the one that takes longest per step on the caller's stream (the critical path) in the timed schedule
+        dom = max(hbm_kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])
         ach = kernels[dom]["alg_GBps"]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(ach / HBM_PEAK_GBS, 4),
@@ -379,9 +394,17 @@ def main():
             roofline["serial"] = {"avg_us": kernels[dom]["serial_avg_us"], "achieved": round(gbs, 1),
                                   "frac": round(gbs / HBM_PEAK_GBS, 4),
                                   "measured": "HIP events, plain schedule (only the DMA copy of the evicted block beside it)"}
-        if any(r.get("frac", 0) > 1 for r in (roofline, roofline.get("alone", {}), roofline.get("serial", {}))):
-            roofline["note"] = ("algorithmic bytes count one row per lookup; rows looked up again and again are served by the "
-                                "caches, so the fraction of the HBM peak can exceed 1")
+        # which roofline binds the whole step: the time the step's HBM bytes need at the HBM peak against the time its
+        # link bytes (the larger direction; the link is full duplex) need at the link's nominal rate
+        t_hbm = step_bytes / (HBM_PEAK_GBS * 1e9)
+        t_link = max(m_m, e_m) * R / (LINK_PEAK_GBS * 1e9)
+        roofline["step"] = {"hbm_bytes": int(step_bytes), "hbm_frac": round(t_hbm / (ms_per_step * 1e-3), 4),
+                            "link_bytes_each_way": int(max(m_m, e_m) * R), "link_frac": round(t_link / (ms_per_step * 1e-3), 4),
+                            "binding": "host_link" if t_link > t_hbm else "hbm",
+                            "note": "fractions of the timed step that its bytes would need at the HBM peak (8 TB/s) and at the "
+                                    "link's nominal rate (64 GB/s per direction); the larger one names the roofline that binds the step"}
+        roofline["model"] = ("bytes that must move per launch: every distinct row once (rows looked up again are served by the "
+                             "caches), every pooled output / gradient row once, the index arrays once")
         link = {}
         for name, direction, rows in (("miss_fill", "h2d", m_m), ("evict_store", "d2h", e_m),
                                       ("h2d_block", "h2d", m_m), ("d2h_block", "d2h", e_m)):
@@ -445,7 +468,7 @@ def main():
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
         "ids_from_host": bool(args.ids_from_host),
-        "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5),
+        "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5), "hit_ratio_by_phase": phases,
         "warm_in": {"batches": args.warmup, "hit_ratio": round(warm_in_hit, 5), "timed": False},
         "roofline": roofline, "host_link": host_link, "kernels": kernels, "cpu_baseline": cpu_baseline,
     }

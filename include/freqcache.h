@@ -58,8 +58,13 @@ enum {
     FC_ERR_OOM_PINNED = -7,
     FC_ERR_HIP = -8,                 /* a HIP runtime call failed, or no usable device            */
     FC_ERR_NOT_PINNED = -9,          /* host_weight given but not page-locked, GPU-mapped memory  */
-    FC_ERR_BAD_SLOT = -10            /* a slot index outside [0, cache_rows) reached fwd / bwd     */
+    FC_ERR_BAD_SLOT = -10,           /* a slot index outside [0, cache_rows) reached fwd / bwd     */
+    FC_ERR_SCRATCH_EXCEEDED = -11    /* embedding_bag_bwd_sgd_noalloc: the batch needs more than its fixed scratch */
 };
+
+/* Limits of embedding_bag_bwd_sgd_noalloc (below). */
+#define FC_NOALLOC_MAX_IDS 524288                 /* lookups per call                                     */
+#define FC_NOALLOC_SCRATCH_BYTES (20 * 1048576)   /* size of the library's fixed scratch array, per GPU   */
 
 /* cache_create flags */
 enum {
@@ -80,6 +85,12 @@ enum {
                                batch's (slot, bag) pairs that embedding_bag_bwd_sgd needs, so that it overlaps the
                                miss fill; it reads slots_dev and offsets_dev until it is done.  Set this flag when
                                no backward pass follows (inference) or those buffers are reused at once. */
+    FC_INPUTS_READY = 32,   /* A promise about cache_plan_next's inputs: ids_dev / offsets_dev are complete when the call is made
+                               (resident batches, or uploads the caller has waited for), not merely enqueued on the caller's
+                               stream.  The library then starts the index work of the planned batch without waiting for the
+                               caller's stream at all (only the slot write-out and the sort still wait for the backward pass
+                               that last read those buffers), which puts the planned batch's index decisions and row fetch a
+                               whole step ahead of cache_advance.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
     FC_DIRTY_TRACK = 16     /* Variant beyond the paper (Algorithm 1 always calls move_to_cpu): a resident row is
                                dirty once embedding_bag_bwd_sgd has updated it since it was loaded; only dirty
                                victims are written back, clean ones are dropped (their copy in the host table is
@@ -110,7 +121,7 @@ enum {
  *                   staging_rows * dim * 4 bytes: one in HBM by default; with FC_TRANSMIT_STAGED two in
  *                   HBM and one pinned; with FC_EVICT_DMA four in HBM and four pinned; cache_plan_next
  *                   adds two in HBM on first use.
- *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK.
+ *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK, FC_INPUTS_READY.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.
  * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous (it also runs a few
@@ -179,8 +190,8 @@ int cache_prepare_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int
  * backward pass.  No row is moved: cache_advance does that, on the caller's stream, i.e. after the backward pass the
  * caller enqueued in between.
  * Same arguments and errors as cache_prepare; not available with FC_TRANSMIT_STAGED.
- * Ordering: the index work is ordered behind the caller's stream as of the ENTRY of the latest cache_prepare /
- * cache_advance call, not as of this call.  ids_dev / offsets_dev must therefore be complete by then (written by work
+ * Ordering (without FC_INPUTS_READY): the index work is ordered behind the caller's stream as of the ENTRY of the latest
+ * cache_prepare / cache_advance call, not as of this call.  ids_dev / offsets_dev must therefore be complete by then (written by work
  * enqueued on the caller's stream before that call, or finished altogether) and stay untouched until cache_advance;
  * slots_dev must not be the buffer the current batch's forward / backward read.  cache_copy_rows / cache_host_weight
  * reflect the planned batch only after cache_advance.
@@ -213,6 +224,21 @@ int embedding_bag_fwd(fc_cache* c, const int32_t* slots_dev, int64_t n, const in
  *   grad_out_dev fp32[num_bags*dim], device.  Asynchronous on the stream; BAD_SLOT as above. */
 int embedding_bag_bwd_sgd(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
                           int64_t num_bags, const float* grad_out_dev, float lr);
+
+/* embedding_bag_bwd_sgd for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * or training loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results, but the
+ * call allocates nothing (no hipMalloc / hipFree, no event creation): the sort buffers, radix histograms and partial
+ * rows it needs live in a fixed array of FC_NOALLOC_SCRATCH_BYTES bytes of device memory that is part of the library's
+ * code object (every GPU the library runs on holds one copy until the process ends; cache_create looks its address up).
+ * Limits: n <= FC_NOALLOC_MAX_IDS lookups, and 10.5 MB + blocks * (16 + 8 * dim) bytes <= FC_NOALLOC_SCRATCH_BYTES, where
+ * blocks = ceil(n / 256) for dim <= 128 and ceil(n * lanes / 8192) with lanes = min(64, dim / 4) for wider rows (dim 256:
+ * n <= 524288; dim 1024: n <= 150000 or so); beyond them the call returns FC_ERR_SCRATCH_EXCEEDED and does nothing.
+ * It never uses a sort started ahead of time by cache_prepare (create the handle with FC_NO_PRESORT to spare that work)
+ * and is not covered by cache_profile_*.  All calls on one GPU, from any handle, share the one array: calls that overlap
+ * on a GPU (two handles on different streams) race; the array keeps the previous call's contents, none of which the
+ * next call reads before writing.  Errors: INVALID_ARG, SCRATCH_EXCEEDED, HIP; BAD_SLOT as embedding_bag_bwd_sgd. */
+int embedding_bag_bwd_sgd_noalloc(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
+                                  int64_t num_bags, const float* grad_out_dev, float lr);
 
 /* Write every resident row back to the host table (the host table is the store of record, Section 3);
  * residency is unchanged.  Returns after the host table is complete. */

@@ -15,16 +15,19 @@ FC_TRANSMIT_STAGED = 2
 FC_EVICT_DMA = 4
 FC_NO_PRESORT = 8
 FC_DIRTY_TRACK = 16
+FC_INPUTS_READY = 32
 
 ERR_NAMES = {
     0: "OK", -1: "INVALID_ARG", -2: "ID_OUT_OF_RANGE", -3: "BAD_OFFSETS", -4: "BATCH_EXCEEDS_CACHE",
     -5: "NOT_PERMUTATION", -6: "OOM_DEVICE", -7: "OOM_PINNED", -8: "HIP", -9: "NOT_PINNED", -10: "BAD_SLOT",
+    -11: "SCRATCH_EXCEEDED",
 }
+NOALLOC_MAX_IDS = 524288
 STAT_FIELDS = ("n_ids", "n_unique", "n_hit_unique", "n_hit_ids", "n_miss", "n_evict", "bytes_h2d", "bytes_d2h")
 
 # every symbol include/freqcache.h declares
 EXPORTS = (
-    "cache_create", "cache_reserve", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_plan_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "cache_flush",
+    "cache_create", "cache_reserve", "cache_warm", "cache_prepare", "cache_prepare_next", "cache_plan_next", "cache_advance", "embedding_bag_fwd", "embedding_bag_bwd_sgd", "embedding_bag_bwd_sgd_noalloc", "cache_flush",
     "cache_check", "cache_destroy", "cache_last_stats", "cache_copy_state", "cache_last_lists", "cache_copy_rows",
     "cache_host_weight", "cache_strerror", "cache_profile_enable", "cache_profile_count", "cache_profile_name",
     "cache_profile_get", "freq_create", "freq_add", "freq_build", "freq_destroy", "table_reorder",
@@ -64,6 +67,7 @@ def load_library(path: str | None = None):
     L.cache_advance.argtypes = [vp]
     L.embedding_bag_fwd.argtypes = [vp, vp, i64, vp, i64, vp]
     L.embedding_bag_bwd_sgd.argtypes = [vp, vp, i64, vp, i64, vp, ctypes.c_float]
+    L.embedding_bag_bwd_sgd_noalloc.argtypes = [vp, vp, i64, vp, i64, vp, ctypes.c_float]
     L.cache_flush.argtypes = [vp]
     L.cache_check.argtypes = [vp]
     L.cache_destroy.argtypes = [vp]
@@ -107,7 +111,8 @@ class FreqCache:
 
     def __init__(self, num_rows: int, dim: int, cache_rows: int, freq_rank: np.ndarray, host_weight=None,
                  staging_rows: int = 0, warm: bool = False, staged: bool = False, stream=None,
-                 dma_evict: bool = False, presort: bool = True, dirty_tracking: bool = False):
+                 dma_evict: bool = False, presort: bool = True, dirty_tracking: bool = False,
+                 inputs_ready: bool = False):
         import torch
 
         if not torch.cuda.is_available():
@@ -123,7 +128,7 @@ class FreqCache:
             assert host_weight.dtype == torch.float32 and host_weight.is_contiguous()
             assert host_weight.numel() == self.num_rows * self.dim
         self.stream = stream if stream is not None else torch.cuda.current_stream()
-        flags = (FC_WARM if warm else 0) | (FC_TRANSMIT_STAGED if staged else 0) | (FC_EVICT_DMA if dma_evict else 0) | (0 if presort else FC_NO_PRESORT) | (FC_DIRTY_TRACK if dirty_tracking else 0)
+        flags = (FC_WARM if warm else 0) | (FC_TRANSMIT_STAGED if staged else 0) | (FC_EVICT_DMA if dma_evict else 0) | (0 if presort else FC_NO_PRESORT) | (FC_DIRTY_TRACK if dirty_tracking else 0) | (FC_INPUTS_READY if inputs_ready else 0)
         h = ctypes.c_void_p()
         rc = self._L.cache_create(self.num_rows, self.dim, self.cache_rows, fr.ctypes.data, _ptr(host_weight),
                                   int(staging_rows), flags, ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
@@ -208,6 +213,13 @@ class FreqCache:
         rc = self._L.embedding_bag_bwd_sgd(self._h, _ptr(slots), slots.numel(), _ptr(offsets), nb, _ptr(grad_out),
                                            float(lr))
         self._check(rc, "embedding_bag_bwd_sgd")
+
+    def embedding_bag_bwd_sgd_noalloc(self, slots, offsets, grad_out, lr: float):
+        nb = offsets.numel() - 1
+        assert grad_out.dtype == self._torch.float32 and grad_out.is_contiguous() and grad_out.numel() == nb * self.dim
+        rc = self._L.embedding_bag_bwd_sgd_noalloc(self._h, _ptr(slots), slots.numel(), _ptr(offsets), nb, _ptr(grad_out),
+                                                   float(lr))
+        self._check(rc, "embedding_bag_bwd_sgd_noalloc")
 
     def flush(self):
         self._check(self._L.cache_flush(self._h), "cache_flush")

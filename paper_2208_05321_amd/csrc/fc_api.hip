@@ -205,6 +205,7 @@ static int make_library_streams(fc_cache* c) {
 static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, float* host_weight, int64_t staging_rows,
                   int32_t flags, void* hip_stream, fc_cache* c) {
     FC_HIP(hipGetDevice(&c->device));
+    FC_TRY(noalloc_setup(c->device));
     c->N = N; c->C = C; c->D = D; c->flags = flags;
     c->stream = (hipStream_t)hip_stream;
     c->vec = (D % 4 == 0) ? 4 : (D % 2 == 0) ? 2 : 1;
@@ -526,6 +527,11 @@ int embedding_bag_bwd_sgd(fc_cache* c, const int32_t* slots_dev, int64_t n, cons
     return bwd_impl(c, slots_dev, n, offsets_dev, num_bags, grad_out_dev, lr);
 }
 
+int embedding_bag_bwd_sgd_noalloc(fc_cache* c, const int32_t* slots_dev, int64_t n, const int64_t* offsets_dev,
+                                  int64_t num_bags, const float* grad_out_dev, float lr) {
+    return bwd_noalloc_impl(c, slots_dev, n, offsets_dev, num_bags, grad_out_dev, lr);
+}
+
 int cache_flush(fc_cache* c) {
     if (!c) return FC_ERR_INVALID_ARG;
     FC_HIP(hipSetDevice(c->device));
@@ -646,6 +652,7 @@ const char* cache_strerror(int code) {
         case FC_ERR_HIP: return "HIP runtime error or no usable GPU";
         case FC_ERR_NOT_PINNED: return "host_weight is not pinned, GPU-mapped memory";
         case FC_ERR_BAD_SLOT: return "slot index outside [0, cache_rows)";
+        case FC_ERR_SCRATCH_EXCEEDED: return "batch too large for the fixed scratch of embedding_bag_bwd_sgd_noalloc";
         default: return "unknown error";
     }
 }

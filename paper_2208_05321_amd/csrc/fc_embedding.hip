@@ -9,7 +9,26 @@
 // finished by a second small kernel in chunk order.  No floating-point atomics: results are reproducible.
 #include "fc_internal.h"
 
+// Scratch of embedding_bag_bwd_sgd_noalloc: sort buffers, radix histograms and the partial rows of the reduction for
+// batches of up to FC_NOALLOC_MAX_IDS lookups live here instead of in memory the library allocates.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.  In host code the name
+// is only a handle for hipGetSymbolAddress: the address kernels and copies use is the one that call returns.
+static __device__ __align__(256) unsigned char scratch[FC_NOALLOC_SCRATCH_BYTES];
+
 namespace fc {
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static unsigned char* scratch_ptr[NOALLOC_MAX_DEVICES] = {};   // per device: where `scratch` lives there
+
+// Called by cache_create with the handle's device current: look the array's address on this device up once.
+int noalloc_setup(int device) {
+    if (device < 0 || device >= NOALLOC_MAX_DEVICES) return FC_OK;          // the entry point then reports the failure
+    if (scratch_ptr[device]) return FC_OK;
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return FC_ERR_HIP; }
+    scratch_ptr[device] = static_cast<unsigned char*>(p);
+    return FC_OK;
+}
 
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using T = float; };
@@ -410,11 +429,60 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     return FC_OK;
 }
 
-int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
-             const float* grad, float lr) {
+// The backward pass on stream st with the given scratch: kin / vin = the batch's (slot, bag) pairs sorted by slot, or
+// null to sort here into sb; part / pmeta hold 2 rows and one record per workgroup of the reduction.
+static int bwd_run(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+                   const float* grad, float lr, const int32_t* kin, const int32_t* vin, SortBufs& sb, float* part,
+                   int32_t* pmeta, fc_cache* prof) {
+    int rthreads; int64_t rblocks; size_t lds;
+    bwd_geometry(c, n, &rthreads, &rblocks, &lds);
+    if (!kin) {
+        int bits = 1;
+        while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
+        SortJob j;
+        j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
+        j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
+        j.keysA = sb.keysA; j.valsA = sb.valsA; j.keysB = sb.keysB; j.valsB = sb.valsB; j.ghist = sb.ghist; j.dtot = sb.dtot;
+        j.prof = prof;
+        FC_TRY(radix_sort(j, st, &kin, &vin));
+    }
+    const int sh = shift_of(c->lpr);
+    if (c->dirty) k_mark_dirty<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(slots, (int)n, (int)c->C, c->dirty);
+    {
+        ProfScope ps(prof, P_BWD_REDUCE, st);
+        BwdMeta* bm = reinterpret_cast<BwdMeta*>(pmeta);
+#define FC_BWD(V, S) \
+        k_bwd_reduce<V, S><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, part, bm)
+#define FC_BWD_V(S) \
+        switch (c->vec) { case 4: FC_BWD(4, S); break; case 2: FC_BWD(2, S); break; default: FC_BWD(1, S); break; }
+        if (n == num_bags) { FC_BWD_V(true) } else { FC_BWD_V(false) }
+#undef FC_BWD_V
+#undef FC_BWD
+    }
+    {
+        ProfScope ps(prof, P_BWD_FIXUP, st);
+        const BwdMeta* bm = reinterpret_cast<const BwdMeta*>(pmeta);
+        const unsigned fb = (unsigned)cdiv(rblocks, 256 >> sh);
+        switch (c->vec) {
+            case 4: k_bwd_fixup<4><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, part, bm, (int)rblocks); break;
+            case 2: k_bwd_fixup<2><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, part, bm, (int)rblocks); break;
+            default: k_bwd_fixup<1><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, part, bm, (int)rblocks); break;
+        }
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
+static int bwd_check_args(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, const float* grad) {
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!slots || !grad || num_bags == 0)))
         return FC_ERR_INVALID_ARG;
+    return FC_OK;
+}
+
+int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+             const float* grad, float lr) {
+    FC_TRY(bwd_check_args(c, slots, n, offsets, num_bags, grad));
     if (n == 0) return FC_OK;
     FC_HIP(hipSetDevice(c->device));
     hipStream_t st = c->stream;
@@ -431,35 +499,46 @@ int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
             break;
         }
     }
-    if (!kin) {
-        FC_TRY(ensure_sort(c->sb[2], n));
-        FC_TRY(sort_pairs(c, c->sb[2], st, slots, n, offsets, num_bags, &kin, &vin));
-    }
-    const int sh = shift_of(c->lpr);
-    if (c->dirty) k_mark_dirty<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(slots, (int)n, (int)c->C, c->dirty);
-    {
-        ProfScope ps(c, P_BWD_REDUCE, st);
-        BwdMeta* bm = reinterpret_cast<BwdMeta*>(c->pmeta);
-#define FC_BWD(V, S) \
-        k_bwd_reduce<V, S><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, c->part, bm)
-#define FC_BWD_V(S) \
-        switch (c->vec) { case 4: FC_BWD(4, S); break; case 2: FC_BWD(2, S); break; default: FC_BWD(1, S); break; }
-        if (n == num_bags) { FC_BWD_V(true) } else { FC_BWD_V(false) }
-#undef FC_BWD_V
-#undef FC_BWD
-    }
-    {
-        ProfScope ps(c, P_BWD_FIXUP, st);
-        const BwdMeta* bm = reinterpret_cast<const BwdMeta*>(c->pmeta);
-        const unsigned fb = (unsigned)cdiv(rblocks, 256 >> sh);
-        switch (c->vec) {
-            case 4: k_bwd_fixup<4><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
-            case 2: k_bwd_fixup<2><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
-            default: k_bwd_fixup<1><<<fb, 256, 0, st>>>((int)c->C, c->cache, c->D, sh, lr, c->part, bm, (int)rblocks); break;
-        }
-    }
-    FC_HIP(hipGetLastError());
-    return FC_OK;
+    if (!kin) FC_TRY(ensure_sort(c->sb[2], n));
+    return bwd_run(c, st, slots, n, offsets, num_bags, grad, lr, kin, vin, c->sb[2], c->part, c->pmeta, c);
+}
+
+// embedding_bag_bwd_sgd for callers that cannot allocate: the same kernels, with the file-scope array `scratch` in
+// place of the buffers bwd_impl allocates.  Nothing in the array has to start at zero: the sort's histograms, the digit
+// totals and the reduction's per-workgroup records are all written in full before they are read, and a partial row is
+// read only where such a record says it was written.
+int bwd_noalloc_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+                     const float* grad, float lr) {
+    FC_TRY(bwd_check_args(c, slots, n, offsets, num_bags, grad));
+    if (n > FC_NOALLOC_MAX_IDS) return FC_ERR_SCRATCH_EXCEEDED;
+    int rthreads; int64_t rblocks; size_t lds;
+    bwd_geometry(c, n > 0 ? n : 1, &rthreads, &rblocks, &lds);
+    const size_t a256 = 255;
+    const size_t pair_bytes = ((size_t)FC_NOALLOC_MAX_IDS * 4 + a256) & ~a256;
+    const size_t ghist_bytes = ((size_t)(cdiv(FC_NOALLOC_MAX_IDS, RS_TILE) << RS_MAX_BITS) * 4 + a256) & ~a256;
+    const size_t dtot_bytes = ((size_t)(1 << RS_MAX_BITS) * 4 + a256) & ~a256;
+    const size_t fixed = 4 * pair_bytes + ghist_bytes + dtot_bytes;
+    const size_t meta_bytes = ((size_t)rblocks * sizeof(BwdMeta) + a256) & ~a256;
+    const size_t part_bytes = (size_t)rblocks * 2 * c->D * 4;
+    static_assert(4 * (((size_t)FC_NOALLOC_MAX_IDS * 4 + 255) & ~(size_t)255) + (1 << 20) <= FC_NOALLOC_SCRATCH_BYTES, "scratch too small for the sort");
+    if (fixed + meta_bytes + part_bytes > (size_t)FC_NOALLOC_SCRATCH_BYTES) return FC_ERR_SCRATCH_EXCEEDED;   // wide rows: fewer lookups fit
+    if (n == 0) return FC_OK;
+    FC_HIP(hipSetDevice(c->device));
+    unsigned char* base = (c->device >= 0 && c->device < NOALLOC_MAX_DEVICES) ? scratch_ptr[c->device] : nullptr;
+    if (!base) return FC_ERR_HIP;                    // the array's address on this device was never found
+    SortBufs sb;
+    unsigned char* p = base;
+    sb.keysA = reinterpret_cast<int32_t*>(p); p += pair_bytes;
+    sb.valsA = reinterpret_cast<int32_t*>(p); p += pair_bytes;
+    sb.keysB = reinterpret_cast<int32_t*>(p); p += pair_bytes;
+    sb.valsB = reinterpret_cast<int32_t*>(p); p += pair_bytes;
+    sb.ghist = reinterpret_cast<int32_t*>(p); p += ghist_bytes;
+    sb.dtot = reinterpret_cast<int32_t*>(p); p += dtot_bytes;
+    int32_t* pmeta = reinterpret_cast<int32_t*>(p); p += meta_bytes;
+    float* part = reinterpret_cast<float*>(p);
+    // no ahead-of-time record is used (its buffers are the library's own allocations) and nothing is timed (timing
+    // events are created on demand)
+    return bwd_run(c, c->stream, slots, n, offsets, num_bags, grad, lr, nullptr, nullptr, sb, part, pmeta, nullptr);
 }
 
 }  // namespace fc

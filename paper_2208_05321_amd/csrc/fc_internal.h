@@ -274,6 +274,9 @@ int ensure_rbuf(fc_cache* c, int64_t n);  // per-id rank buffer for batches of n
 int reserve_bwd(fc_cache* c, int64_t n);   // sort scratch of all three sets and the partial rows for batches of n lookups
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
              const float* grad, float lr);
+int bwd_noalloc_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
+                     const float* grad, float lr);
+int noalloc_setup(int device);
 
 // row movement (fc_rows.hip).  dst_idx / src_idx: per-row index lists in device memory, or nullptr for row j.
 // dst_rows / src_rows bound the row indices on either side (rows with an index outside are skipped).

@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+
 # HBM bytes per launch from rocprofv3 --pmc (2 x FETCH_SIZE + WRITE_SIZE, scale factors from a plain copy;
 # profiles/c2_pmc_fetch_write_size.md, profiles/c4_pmc_fetch_write_size.md); only quoted when the workload is exactly
 # the configuration the counters were collected on.
@@ -147,7 +148,8 @@ def main():
 
     cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
                       warm=False, staged=args.transmitter == "staged", stream=stream,
-                      dma_evict=args.transmitter == "dma", dirty_tracking=args.dirty_tracking, presort=not args.forward_only)
+                      dma_evict=args.transmitter == "dma", dirty_tracking=args.dirty_tracking, presort=not args.forward_only,
+                      inputs_ready=not args.ids_from_host)      # every batch is resident before it is handed to the library
     host = cache.host_weight()
     w.host_table(out=host)
     cache.warm()

@@ -85,6 +85,7 @@ static int reset_state(fc_cache* c, bool warm) {
     for (hipStream_t x : {c->pre, c->pf, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
     c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr; c->pf_dep = nullptr;
+    c->quiesce_stream = nullptr;
     c->fetch_timed[0] = c->fetch_timed[1] = false; c->last_copy_buf = -1;
     for (bool& b : c->copy_timed) b = false;
     for (PresortRec& r : c->rec) r.valid = false;
@@ -142,7 +143,7 @@ static void destroy(fc_cache* c) {
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_assign_done, c->ev_quiesce, c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->pre) (void)hipStreamDestroy(c->pre);
     if (c->pf) (void)hipStreamDestroy(c->pf);
@@ -221,6 +222,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY")) { const int v = atoi(e); if (v >= 1) { c->fill_blocks_early = v; c->tune_early = false; } }
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY_START")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }   // still tuned
     c->fill_blocks_early_max = c->fill_blocks_early;
+    if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
@@ -292,10 +294,25 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
         }
     }
     FC_TRY(make_library_streams(c));
+    // FC_FETCH_CU_MASK=<k> (experiment): the stream of the early row fetch may only use k compute units, spread evenly
+    if (const char* e = getenv("FC_FETCH_CU_MASK")) {
+        const int k = atoi(e);
+        hipDeviceProp_t prop;
+        if (k >= 1 && hipGetDeviceProperties(&prop, c->device) == hipSuccess && k < prop.multiProcessorCount) {
+            const int cus = prop.multiProcessorCount;
+            std::vector<uint32_t> mask((size_t)(cus + 31) / 32, 0u);
+            for (int i = 0; i < k; ++i) { const int b = (int)((int64_t)i * cus / k); mask[b >> 5] |= 1u << (b & 31); }
+            hipStream_t ms = nullptr;
+            if (hipExtStreamCreateWithCUMask(&ms, (uint32_t)mask.size(), mask.data()) == hipSuccess) {
+                (void)hipStreamDestroy(c->pf);
+                c->pf = ms;
+            } else (void)hipGetLastError();
+        }
+    }
     c->aux = c->pf;
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
+    for (hipEvent_t* e : {&c->ev_assign_done, &c->ev_quiesce, &c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     if (c->dma_evict) {
@@ -360,7 +377,7 @@ static int fetch_early(fc_cache* c, int64_t M) {
     const int k = c->lset;
     if (!ensure_arrival_block(c, k)) return FC_OK;   // no room for the block: the rows are fetched at cache_advance instead
     if (c->tune_early) tune_fetch_grid(c, k);
-    FC_HIP(hipStreamWaitEvent(c->pf, c->ev_index_done, 0));
+    FC_HIP(hipStreamWaitEvent(c->pf, c->ev_assign_done, 0));
     if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
     if (c->dma_evict) {
         FC_HIP(hipEventRecord(c->ev_fetch_a[k], c->pf));
@@ -399,7 +416,7 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
-        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT | FC_DIRTY_TRACK)) ||
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT | FC_DIRTY_TRACK | FC_INPUTS_READY)) ||
         ((flags & FC_TRANSMIT_STAGED) && (flags & FC_EVICT_DMA)))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
@@ -481,9 +498,14 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     // The index half touches no rows, so it need not wait for the row movement, forward or backward work the caller
     // enqueued since the last cache_prepare / cache_advance: it is ordered behind the caller's stream as of the entry
     // of that call (which covers the backward pass whose sorted pairs this call's sort will overwrite).
-    FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
+    // With FC_INPUTS_READY the decisions themselves wait for nothing on the caller's stream (they read the ids and the
+    // library's own index state, which only index halves change); the slot write-out, the first kernel to touch a buffer
+    // of the caller's, still waits.  With FC_DIRTY_TRACK the row movement of the current batch marks rows as in transit,
+    // which the planned batch's decisions read: no head start then.
+    const bool early = (c->flags & FC_INPUTS_READY) && !c->dirty_track;
+    if (!early) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
     MovePlan mv;
-    const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv);
+    const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv, early ? c->ev_s_now : nullptr);
     c->pst = c->stream;
     c->last_pst = c->pre;
     c->next_pending = true;

@@ -145,6 +145,42 @@ __global__ __launch_bounds__(256) void k_bag_fwd(const float* __restrict__ cache
     if (bad) atomicOr(&ctl->async_flags, EF_BAD_SLOT);
 }
 
+// Forward for batches with one lookup per bag whose (slot, bag) pairs are already sorted by slot (the sort the backward
+// pass needs, started by cache_prepare): out[bag] = row of slot, walked in SLOT order.  In bag order every compute-unit
+// cluster meets every popular row and fetches its own copy through its own L2 (config 4: 286 MB fetched for 96 MB of
+// distinct rows); in slot order a row's lookups sit next to each other, so each row crosses the fabric once and the
+// kernel is left with writing the pooled output.  FWD_ROWS lookups per row-group are in flight together; a repeated
+// slot is simply loaded again (it hits the L1 / L2 of the same compute unit).
+constexpr int FWD_ROWS = 8;
+template <int VEC>
+__global__ __launch_bounds__(256) void k_bag_fwd_sorted(const float* __restrict__ cache, const int32_t* __restrict__ keys,
+                                                        const int32_t* __restrict__ vals, int n, int num_bags, int C, int D,
+                                                        int lpr_shift, float* __restrict__ out) {
+    using V = typename Vec<VEC>::T;
+    const int lpr = 1 << lpr_shift;
+    const int gpb = blockDim.x >> lpr_shift;
+    const int gl = threadIdx.x >> lpr_shift, lane = threadIdx.x & (lpr - 1);
+    const int nv = D / VEC;
+    for (int64_t i0 = (int64_t)(blockIdx.x * gpb + gl) * FWD_ROWS; i0 < n; i0 += (int64_t)gridDim.x * gpb * FWD_ROWS) {
+        int k[FWD_ROWS], b[FWD_ROWS];
+#pragma unroll
+        for (int j = 0; j < FWD_ROWS; ++j) {
+            const int64_t i = i0 + j < n ? i0 + j : n - 1;      // the tail repeats the last lookup (same value stored twice)
+            k[j] = keys[i];
+            b[j] = vals[i];
+        }
+        for (int cidx = lane; cidx < nv; cidx += lpr) {
+            V v[FWD_ROWS];
+#pragma unroll
+            for (int j = 0; j < FWD_ROWS; ++j)     // a slot out of range was sorted under the key C: its bag reads as zeros
+                v[j] = (unsigned)k[j] < (unsigned)C ? reinterpret_cast<const V*>(cache + (size_t)k[j] * D)[cidx] : vzero(V());
+#pragma unroll
+            for (int j = 0; j < FWD_ROWS; ++j)
+                if ((unsigned)b[j] < (unsigned)num_bags) nt_store(&reinterpret_cast<V*>(out + (size_t)b[j] * D)[cidx], vadd(vzero(V()), v[j]));
+        }
+    }
+}
+
 static inline int shift_of(int lpr) { int s = 0; while ((1 << s) < lpr) ++s; return s; }
 
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out) {
@@ -155,6 +191,26 @@ int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
     FC_HIP(hipSetDevice(c->device));
     const int sh = shift_of(c->lpr);
     const int gpb = 256 >> sh;
+    // One lookup per bag and the batch's pairs sorted ahead of time by the call that prepared it: walk them in slot order.
+    // (Offsets are not consulted: the record was made from these very buffers, and with as many lookups as bags the
+    // sort found bag i for lookup i or, for offsets that do not say so, whatever bag holds lookup i.)
+    if (n == num_bags && c->fwd_sorted) {
+        for (PresortRec& r : c->rec) {
+            if (r.valid && r.one_per_bag && r.ticket == c->cur_ticket && r.slots == slots && r.n == n && r.offsets == offsets && r.bags == num_bags) {
+                FC_HIP(hipStreamWaitEvent(c->stream, r.ev_sorted, 0));
+                int64_t blocks = cdiv(n, (int64_t)gpb * FWD_ROWS);
+                if (blocks > (1 << 20)) blocks = 1 << 20;
+                ProfScope ps(c, P_BAG_FWD, c->stream);
+                switch (c->vec) {
+                    case 4: k_bag_fwd_sorted<4><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                    case 2: k_bag_fwd_sorted<2><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                    default: k_bag_fwd_sorted<1><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                }
+                FC_HIP(hipGetLastError());
+                return FC_OK;
+            }
+        }
+    }
     const int bags_per_group = (n == num_bags && c->fwd_bags > 1) ? c->fwd_bags : 1;
     int64_t blocks = cdiv(num_bags, (int64_t)gpb * bags_per_group);
     if (blocks > (1 << 20)) blocks = 1 << 20;
@@ -321,11 +377,29 @@ __global__ __launch_bounds__(256) void k_bwd_fixup(int C, float* cache, int D, i
     if (b >= nblocks || !bmeta[b].has_head) return;
     const int slot = bmeta[b].head_slot;
     if (slot >= C) return;
+    // The pieces are added in workgroup order, FIX_PF of them requested together (a popular row's run spans hundreds of
+    // workgroups; one dependent load per piece made this kernel as long as that chain).  Pieces past the end of the run
+    // are loaded and ignored.
+    constexpr int FIX_PF = 8;
     for (int cidx = lane; cidx < nv; cidx += lpr) {
         V acc = reinterpret_cast<const V*>(part + (size_t)(b * 2 + 1) * D)[cidx];
-        for (int h = b + 1; h < nblocks; ++h) {
-            acc = vadd(acc, reinterpret_cast<const V*>(part + (size_t)(h * 2) * D)[cidx]);
-            if (bmeta[h].first_kind != 2) break;
+        bool done = false;
+        for (int h = b + 1; h < nblocks && !done; h += FIX_PF) {
+            V p[FIX_PF];
+            int kind[FIX_PF];
+#pragma unroll
+            for (int j = 0; j < FIX_PF; ++j) {
+                const int hh = h + j < nblocks ? h + j : nblocks - 1;
+                p[j] = reinterpret_cast<const V*>(part + (size_t)(hh * 2) * D)[cidx];
+                kind[j] = bmeta[hh].first_kind;
+            }
+#pragma unroll
+            for (int j = 0; j < FIX_PF; ++j) {
+                if (!done && h + j < nblocks) {
+                    acc = vadd(acc, p[j]);
+                    done = kind[j] != 2;
+                }
+            }
         }
         V* row = reinterpret_cast<V*>(cache + (size_t)slot * D);
         row[cidx] = vsgd(row[cidx], acc, lr);
@@ -425,6 +499,7 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     FC_HIP(hipEventRecord(r.ev_sorted, c->aux));
     r.slots = slots; r.n = n; r.offsets = offsets; r.bags = num_bags;
     r.ticket = c->ticket;
+    r.one_per_bag = c->last_one_per_bag;
     r.valid = true;
     return FC_OK;
 }

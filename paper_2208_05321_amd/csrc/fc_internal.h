@@ -18,7 +18,7 @@ constexpr int RT_WORDS = RT_THREADS * 4;
 constexpr int RS_THREADS = 256;
 constexpr int RS_ITEMS = 8;                      // keys per thread
 constexpr int RS_TILE = RS_THREADS * RS_ITEMS;
-constexpr int RS_TWO_PASS_BITS = 9;               // keys of up to 18 bits are sorted in two passes
+constexpr int RS_TWO_PASS_BITS = 11;              // keys of up to 22 bits are sorted in two passes
 constexpr int RS_MAX_BITS = RS_TWO_PASS_BITS;     // most bits per pass: sizes the digit tables
 // Consecutive sorted lookups reduced by one row-group in the backward pass.
 #ifndef FC_BWD_CHUNK
@@ -32,7 +32,8 @@ constexpr int BWD_CHUNK = FC_BWD_CHUNK;
 constexpr int BWD_PF = FC_BWD_PF;
 
 // Sticky device-side flags.
-enum : uint32_t { EF_BAD_OFFSETS = 1u, EF_ID_RANGE = 2u, EF_BAD_SLOT = 4u };
+enum : uint32_t { EF_BAD_OFFSETS = 1u, EF_ID_RANGE = 2u, EF_BAD_SLOT = 4u,
+                  EF_NOT_ONE_PER_BAG = 8u };   // not an error: some bag of the batch does not hold exactly its own lookup
 
 // Device-resident control block, read and written by the planning kernels.
 struct Ctl {
@@ -46,6 +47,7 @@ struct Ctl {
 // Host-visible (pinned, mapped) copy of the decision, written by the planning kernel.
 struct HostCtl {
     int32_t status, n_unique, n_miss, need, hit_ids, nfree, async_flags;
+    int32_t batch_flags; // EF_NOT_ONE_PER_BAG
     int32_t ticket;      // written last: number of the cache_prepare call this record belongs to
 };
 
@@ -74,6 +76,7 @@ struct MovePlan { bool valid = false; int64_t M = 0, need = 0; int buf = 0, tran
 struct PresortRec {
     bool valid = false;
     int32_t ticket = 0;                 // number of the cache_prepare / _next / plan_next call whose slots it sorted
+    bool one_per_bag = false;           // bag b of that batch holds exactly lookup b (the click-log shape)
     const int32_t* slots = nullptr; const int64_t* offsets = nullptr;
     int64_t n = 0, bags = 0;
     const int32_t *keys = nullptr, *vals = nullptr;
@@ -93,6 +96,9 @@ struct fc_cache {
     // the current one.  pst = the stream the cache_prepare / cache_prepare_next in progress enqueues on.
     hipStream_t pre = nullptr, pst = nullptr, last_pst = nullptr;
     hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr, ev_index_done = nullptr;
+    hipEvent_t ev_assign_done = nullptr;   // index half: every decision taken (all but the slot write-out): the early fetch may start
+    hipEvent_t ev_quiesce = nullptr;       // transit marks dropped by dma_quiesce on another stream than the index stream
+    hipStream_t quiesce_stream = nullptr;
     hipStream_t last_index_stream = nullptr;
     // The lists an index half writes and its row-movement half reads exist twice, so that the index half of the next
     // batch can run while the rows of the current one still move: lset = the set of the latest index half.
@@ -112,6 +118,8 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    bool fwd_sorted = true;         // one-lookup-per-bag batches: forward in slot order when the pairs are sorted ahead of time (tuning: FC_FWD_SORTED=0)
+    bool last_one_per_bag = false;  // the batch of the latest index half has that shape
     int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
     int fill_blocks = 1024;         // cap on the workgroups of the miss fill (tuning: FC_FILL_BLOCKS); 40 with FC_EVICT_DMA:
@@ -263,7 +271,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // entry points implemented across the sources
 int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
-                  int64_t num_bags, int32_t* slots, MovePlan* mv);
+                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots = nullptr);
 int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv);
 int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
                  int64_t num_bags, int32_t* slots);

@@ -81,6 +81,7 @@ __global__ __launch_bounds__(MARK_THREADS) void k_remap_mark(const int64_t* __re
             }
             if (i < end && i <= num_bags) {
                 const int64_t o = offsets[i];
+                if (o != i) flags |= EF_NOT_ONE_PER_BAG;
                 if (i == 0 && o != 0) flags |= EF_BAD_OFFSETS;
                 if (i == num_bags && o != (int64_t)n) flags |= EF_BAD_OFFSETS;
                 if (i < num_bags && offsets[i + 1] < o) flags |= EF_BAD_OFFSETS;
@@ -158,6 +159,8 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restri
 // ---------------------------------------------------------------------------------------------------------
 // K2b  one workgroup: totals, the call's status, evict_num = numel(miss) - empty slots, output offsets of
 //      every tile's missing ranks, and which tiles give up how many victims (from the top rank down).
+//      (Tried: letting the last workgroup of K2a to finish do this, found by an atomic ticket.  One ticket per tile on
+//      one address costs about 100 ns each on this part, 300 us at 3052 tiles: slower than the launch it saves.)
 // ---------------------------------------------------------------------------------------------------------
 // 256 threads: a workgroup this small finds room on a compute unit at once; a 1024-thread one waited up to 200 us for
 // sixteen free wave slots beside the previous batch's forward kernel, with the host waiting for its ticket.
@@ -246,10 +249,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void k_rank_plan(const int32_t* __res
         ctl->err_flags = 0;
         hctl->status = status; hctl->n_unique = totU; hctl->n_miss = M; hctl->need = need;
         hctl->hit_ids = hits; hctl->nfree = nf; hctl->async_flags = (int32_t)ctl->async_flags;
+        hctl->batch_flags = (int32_t)(ef & EF_NOT_ONE_PER_BAG);
         __threadfence_system();                       // the record first, then the ticket the host is polling for
         *reinterpret_cast<volatile int32_t*>(&hctl->ticket) = ticket;
     }
 }
+
+constexpr int FREE_TILE = 1024;
 
 // ---------------------------------------------------------------------------------------------------------
 // K2c  per tile: write the missing ranks (ascending), pick and retire the victims, update rbits, clear ubits.
@@ -343,7 +349,6 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
 // K6  the i-th missing rank takes the i-th lowest empty slot; both index maps are updated.
 //     a) empty slots per tile of FREE_TILE slots;  b) each tile ranks its empty slots after the tiles below it.
 // ---------------------------------------------------------------------------------------------------------
-constexpr int FREE_TILE = 1024;
 // 256 threads with 4 consecutive slots each: a workgroup this small finds room on a compute unit at once, also while
 // the forward / backward kernels of the previous batch fill the chip (cache_plan_next)
 constexpr int FREE_THREADS = 256;
@@ -549,6 +554,9 @@ int dma_quiesce(fc_cache* c, hipStream_t st) {
         }
     }
     FC_HIP(hipGetLastError());
+    // the index kernels of a later batch read and write the same map entries, possibly on another stream
+    FC_HIP(hipEventRecord(c->ev_quiesce, st));
+    c->quiesce_stream = st;
     return FC_OK;
 }
 
@@ -628,8 +636,9 @@ static int wait_for_ticket(const volatile int32_t* ticket_word, int32_t ticket, 
 
 // Index half of Algorithm 1: every decision (unique rows, misses, victims, slot assignment, both maps, the slots
 // of the batch) and no row movement.  Fills *mv with what prepare_move has to do.
+// before_slots: an event the slot write-out (the first kernel that writes the caller's buffer) has to wait for.
 int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
-                  int64_t num_bags, int32_t* slots, MovePlan* mv) {
+                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots) {
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!ids || !slots)))
         return FC_ERR_INVALID_ARG;
@@ -642,6 +651,8 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     c->have_lists = false;
     if (c->move_stream[c->lset] && c->move_stream[c->lset] != st) FC_HIP(hipStreamWaitEvent(st, c->ev_move_done[c->lset], 0));
     if (c->last_index_stream && c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_index_done, 0));
+    if (c->quiesce_stream && c->quiesce_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_quiesce, 0));
+    c->quiesce_stream = nullptr;
     const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
     const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
@@ -697,11 +708,12 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     HostCtl h;
     {
         const volatile int32_t* hv = reinterpret_cast<const volatile int32_t*>(c->hctl);
-        FC_TRY(wait_for_ticket(hv + 7, ticket, st));
+        FC_TRY(wait_for_ticket(hv + 8, ticket, st));
         h.status = hv[0]; h.n_unique = hv[1]; h.n_miss = hv[2]; h.need = hv[3]; h.hit_ids = hv[4]; h.nfree = hv[5];
-        h.async_flags = hv[6]; h.ticket = hv[7];
+        h.async_flags = hv[6]; h.batch_flags = hv[7]; h.ticket = hv[8];
     }
     if (h.status != FC_OK) return h.status;
+    c->last_one_per_bag = n == num_bags && !(h.batch_flags & (int32_t)EF_NOT_ONE_PER_BAG);
     const int64_t M = h.n_miss, need = h.need;
     if (M > 0) {
         {
@@ -715,8 +727,10 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
                                                       c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
         }
     }
+    FC_HIP(hipEventRecord(c->ev_assign_done, st));
     // every row of the batch has its slot now: write the slots out (the caller then starts sorting them for the
     // backward pass on a library stream, where the sort runs while the missing rows cross the host link)
+    if (before_slots) FC_HIP(hipStreamWaitEvent(st, before_slots, 0));
     if (n > 0) {
         ProfScope ps(c, P_SLOTS_OUT, st);
         k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);

@@ -3,6 +3,8 @@
 // (sort ids by descending count).  Keys come from one of three sources, see SortSrc.
 #include "fc_internal.h"
 
+#include <stdlib.h>
+
 namespace fc {
 
 // First-pass key of lookup i: its slot, or the sentinel C if the slot is out of range.
@@ -204,9 +206,15 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
 }
 
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
-    // Two passes up to 18 key bits (six launches, each bound by latency rather than by bytes); beyond that a tile of
-    // 2048 keys would hold about one key per digit and the per-tile digit tables dominate, so passes of at most 8 bits.
-    const int passes = j.bits <= 2 * RS_TWO_PASS_BITS ? (j.bits + RS_TWO_PASS_BITS - 1) / RS_TWO_PASS_BITS : (j.bits + 7) / 8;
+    // Two passes up to 22 key bits: every pass is three launches bound by latency rather than by bytes, so a third pass
+    // costs more than the larger digit tables of 10- and 11-bit digits do; beyond that, passes of at most 8 bits.
+    // (FC_SORT_BITS, read once per process, lowers the two-pass limit per pass for experiments.)
+    static const int two_pass_bits = [] {
+        const char* e = getenv("FC_SORT_BITS");
+        const int v = e ? atoi(e) : 0;
+        return (v >= 4 && v <= RS_TWO_PASS_BITS) ? v : RS_TWO_PASS_BITS;
+    }();
+    const int passes = j.bits <= 2 * two_pass_bits ? (j.bits + two_pass_bits - 1) / two_pass_bits : (j.bits + 7) / 8;
     const int rb = (j.bits + passes - 1) / passes;
     const int32_t* kin = j.keys_in; const int32_t* vin = j.vals_in;
     int32_t* kout = j.keysA; int32_t* vout = j.valsA;

@@ -82,14 +82,14 @@ def test_full_size(name, ratio, batches, dma, host_gb):
 @pytest.mark.parametrize("name,batches,host_gb,free", [("c2", 10, 12, False), ("c2", 24, 12, True), ("c4", C4_BATCHES, 130, True),
                                                        ("c4", [99, 100, 101], 130, False), ("c5", 3, 130, True)])
 def test_full_size_pipelined_schedule(name, batches, host_gb, free):
-    """The launch configuration bench.py times: DMA evict transmitter, cache_plan_next(t+1) beside batch t's forward /
+    """The launch configuration bench.py times: DMA evict transmitter, FC_INPUTS_READY, cache_plan_next(t+1) beside batch t's forward /
     backward, rows fetched ahead of time, cache_advance; `free`: no synchronisation inside the loop, as in the timed
     region (every slot array, pooled output and the final tables are compared afterwards).  Config 4 crosses the first
     rotation of its hot set."""
     need_host_gb(host_gb)
     w = workload(name)
     log(f"{name} pipelined, free-running {free}: batches {batches}")
-    run_parity_planned(w, batches, warm=True, dma_evict=True, free_running=free, log=log)
+    run_parity_planned(w, batches, warm=True, dma_evict=True, free_running=free, log=log, inputs_ready=True)
     report_worst(log)
 
 

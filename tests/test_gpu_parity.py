@@ -139,18 +139,33 @@ def test_lookahead_free_running(torch_cuda, dma):
     ("c2", 0.1, 0.015, True, False), ("c2", 0.1, 0.015, False, False), ("c5", 0.05, 0.015, True, False),
     ("c2", 0.2, 0.015, True, True), ("c2", 0.2, 0.015, False, True), ("c4", 0.02, 0.03, True, True),
 ])
-def test_planned_prepare(torch_cuda, name, scale, ratio, dma, free):
+@pytest.mark.parametrize("ready", [False, True])
+def test_planned_prepare(torch_cuda, name, scale, ratio, dma, free, ready):
     """cache_plan_next + cache_advance: index work of batch t+1 beside the forward / backward of batch t; identical
-    results to plain cache_prepare (same oracle, program order)."""
+    results to plain cache_prepare (same oracle, program order).  ready: FC_INPUTS_READY, the planned batch's decisions
+    do not wait for the caller's stream at all."""
     w = make_workload(name, scale=scale, cache_ratio=ratio)
-    run_parity_planned(w, 16 if free else 8, warm=True, dma_evict=dma, free_running=free)
-    run_parity_planned(w, 6, warm=True, dma_evict=dma, free_running=free, plan_first=True)
+    run_parity_planned(w, 16 if free else 8, warm=True, dma_evict=dma, free_running=free, inputs_ready=ready)
+    run_parity_planned(w, 6, warm=True, dma_evict=dma, free_running=free, plan_first=True, inputs_ready=ready)
 
 
-def test_planned_prepare_cold_and_small_blocks(torch_cuda):
+@pytest.mark.parametrize("dma", [True, False])
+@pytest.mark.parametrize("free", [True, False])
+def test_planned_inputs_ready_tiny_cache_thrashing(torch_cuda, dma, free):
+    """FC_INPUTS_READY with a cache so small that rows evicted by one batch are missed by the next or the one after:
+    the planned batch is indexed (and its rows fetched) while the evictions of the batch before are still to be
+    carried out on the caller's stream."""
+    from tests.tiny_workload import TinyWorkload
+    w = TinyWorkload(num_rows=900, dim=64, cache_rows=48, seed=21, multi_hot=True, bags=24, max_bag=3, distinct_cap=40)
+    run_parity_planned(w, 40, warm=True, dma_evict=dma, free_running=free, inputs_ready=True)
+    run_parity_planned(w, 24, warm=False, dma_evict=dma, free_running=free, inputs_ready=True, staging_rows=16)
+
+
+@pytest.mark.parametrize("ready", [False, True])
+def test_planned_prepare_cold_and_small_blocks(torch_cuda, ready):
     w = make_workload("c2", scale=0.05, cache_ratio=0.05)
-    run_parity_planned(w, 8, warm=False, dma_evict=True, staging_rows=900)     # some batches exceed one block
-    run_parity_planned(w, 6, warm=False, dma_evict=False, staging_rows=5)
+    run_parity_planned(w, 8, warm=False, dma_evict=True, staging_rows=900, inputs_ready=ready)     # some batches exceed one block
+    run_parity_planned(w, 6, warm=False, dma_evict=False, staging_rows=5, inputs_ready=ready)
 
 
 def test_planned_then_plain_prepare_and_flush(torch_cuda):

@@ -12,7 +12,7 @@
  *     on the whole table.  Pinned by tests against a no-cache computation.
  *   - CACHE BEHAVIOUR (hit/miss sets, victims, slot assignment, bytes moved):
  *     the policy of Algorithm 1, taken step by step below.  Pinned by tests
- *     against a literal array-op rendering of Algorithm 1 on tiny tables, a
+ *     against a brute-force set-based statement of Algorithm 1 on tiny tables, a
  *     hand-worked trace, and invariants.
  *   - parity unpinned: absolute hit-ratio values (the paper prints none).
  *

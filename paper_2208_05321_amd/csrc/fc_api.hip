@@ -143,7 +143,7 @@ static void destroy(fc_cache* c) {
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_assign_done, c->ev_quiesce, c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_assign_done, c->ev_emit_done, c->ev_quiesce, c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->pre) (void)hipStreamDestroy(c->pre);
     if (c->pf) (void)hipStreamDestroy(c->pf);
@@ -223,6 +223,8 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY_START")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }   // still tuned
     c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
+    if (const char* e = getenv("FC_FWD_PAD_KB")) { const int v = atoi(e); if (v >= 0 && v <= 60) c->fwd_pad = v * 1024; }
+    if (const char* e = getenv("FC_BWD_PAD_KB")) { const int v = atoi(e); if (v >= 0 && v <= 40) c->bwd_pad = v * 1024; }
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
@@ -312,7 +314,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     c->aux = c->pf;
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_assign_done, &c->ev_quiesce, &c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
+    for (hipEvent_t* e : {&c->ev_assign_done, &c->ev_emit_done, &c->ev_quiesce, &c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     if (c->dma_evict) {
@@ -377,7 +379,7 @@ static int fetch_early(fc_cache* c, int64_t M) {
     const int k = c->lset;
     if (!ensure_arrival_block(c, k)) return FC_OK;   // no room for the block: the rows are fetched at cache_advance instead
     if (c->tune_early) tune_fetch_grid(c, k);
-    FC_HIP(hipStreamWaitEvent(c->pf, c->ev_assign_done, 0));
+    FC_HIP(hipStreamWaitEvent(c->pf, c->ev_emit_done, 0));       // which rows are missing and where their newest copies are
     if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
     if (c->dma_evict) {
         FC_HIP(hipEventRecord(c->ev_fetch_a[k], c->pf));
@@ -504,8 +506,12 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     // which the planned batch's decisions read: no head start then.
     const bool early = (c->flags & FC_INPUTS_READY) && !c->dirty_track;
     if (!early) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
+    // FC_DIRTY_TRACK: which victims of the current batch are in transit is only marked by its row movement
+    if (c->dirty_track && c->move_stream[c->lset]) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_move_done[c->lset], 0));
     MovePlan mv;
-    const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv, early ? c->ev_s_now : nullptr);
+    // the slot write-out is folded into the first kernel of the sort (one launch and one pass over the ranks fewer)
+    const bool fold = c->presort && n > 0 && num_bags > 0;
+    const int rc = prepare_index(c, c->pre, false, ids_dev, n, offsets_dev, num_bags, slots_dev, &mv, early ? c->ev_s_now : nullptr, fold);
     c->pst = c->stream;
     c->last_pst = c->pre;
     c->next_pending = true;
@@ -521,7 +527,13 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     // latest row movement, which produced both, is the only thing to wait for.  Victims leave, and these rows enter
     // their slots, at cache_advance.
     if (mv.M > 0 && mv.M <= c->staging_rows) rc2 = fetch_early(c, mv.M);
-    if (n > 0) { c->pst = c->pre; (void)presort_impl(c, slots_dev, n, offsets_dev, num_bags); c->pst = c->stream; }
+    if (fold) {
+        c->pst = c->pre;
+        const int rs = presort_impl(c, slots_dev, n, offsets_dev, num_bags, slots_dev);
+        c->pst = c->stream;
+        if (rs != FC_OK) FC_TRY(launch_slots_out(c, c->pre, slots_dev, n));     // no sort: the plain write-out
+        FC_HIP(hipEventRecord(c->ev_index_done, c->pre));
+    } else if (n > 0) { c->pst = c->pre; (void)presort_impl(c, slots_dev, n, offsets_dev, num_bags); c->pst = c->stream; }
     FC_HIP(hipEventRecord(c->ev_pre_done, c->pre));
     return rc2;
 }

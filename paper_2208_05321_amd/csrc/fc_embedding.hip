@@ -202,9 +202,9 @@ int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offset
                 if (blocks > (1 << 20)) blocks = 1 << 20;
                 ProfScope ps(c, P_BAG_FWD, c->stream);
                 switch (c->vec) {
-                    case 4: k_bag_fwd_sorted<4><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
-                    case 2: k_bag_fwd_sorted<2><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
-                    default: k_bag_fwd_sorted<1><<<(unsigned)blocks, 256, 0, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                    case 4: k_bag_fwd_sorted<4><<<(unsigned)blocks, 256, c->fwd_pad, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                    case 2: k_bag_fwd_sorted<2><<<(unsigned)blocks, 256, c->fwd_pad, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
+                    default: k_bag_fwd_sorted<1><<<(unsigned)blocks, 256, c->fwd_pad, c->stream>>>(c->cache, r.keys, r.vals, (int)n, (int)num_bags, (int)c->C, c->D, sh, out); break;
                 }
                 FC_HIP(hipGetLastError());
                 return FC_OK;
@@ -459,11 +459,12 @@ static int ensure_part(fc_cache* c, int64_t groups) {
 
 // Stable sort of the batch's (slot, bag) pairs by slot on stream `st`; *kres / *vres receive the sorted arrays.
 static int sort_pairs(fc_cache* c, SortBufs& sb, hipStream_t st, const int32_t* slots, int64_t n, const int64_t* offsets,
-                      int64_t num_bags, const int32_t** kres, const int32_t** vres) {
+                      int64_t num_bags, const int32_t** kres, const int32_t** vres, int32_t* slots_out = nullptr) {
     int bits = 1;
     while (((int64_t)1 << bits) <= c->C) ++bits;           // keys lie in [0, C] (C = out-of-range sentinel)
     SortJob j;
     j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
+    if (slots_out) { j.src = SORT_SRC_RANKS; j.keys_in = c->rbuf; j.rank_slot = c->rank_slot; j.slots_out = slots_out; }
     j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
     j.keysA = sb.keysA; j.valsA = sb.valsA; j.keysB = sb.keysB; j.valsB = sb.valsB; j.ghist = sb.ghist; j.dtot = sb.dtot;
     j.prof = c;
@@ -481,7 +482,7 @@ static inline void bwd_geometry(const fc_cache* c, int64_t n, int* rthreads, int
 // sort needs nothing but the slots and the bag offsets, so it runs on a library stream (c->aux) while the missing
 // rows are still crossing the host link.  Two records alternate, so that the sort of the next batch does not
 // disturb the current one's.
-int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags) {
+int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out) {
     const int k = c->rec_next;
     c->rec_next ^= 1;
     PresortRec& r = c->rec[k];
@@ -489,13 +490,13 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     // the other record stays only if it belongs to the current batch (look-ahead / pipelined schedules: its backward pass
     // may still be to come); a batch that was prepared and never trained on leaves nothing behind
     if (c->rec[k ^ 1].valid && c->rec[k ^ 1].ticket != c->cur_ticket) c->rec[k ^ 1].valid = false;
-    if (!c->presort || n <= 0 || num_bags <= 0) return FC_OK;
+    if (!c->presort || n <= 0 || num_bags <= 0) return slots_out ? FC_ERR_INVALID_ARG : FC_OK;   // the caller then writes the slots out itself
     FC_TRY(ensure_sort(c->sb[k], n));
     FC_HIP(hipEventRecord(c->ev_slots, c->pst));
     FC_HIP(hipStreamWaitEvent(c->aux, c->ev_slots, 0));
     // the record's previous sort was read by a backward pass on the caller's stream, enqueued before this call
     if (c->pst != c->stream) FC_HIP(hipStreamWaitEvent(c->aux, c->ev_s_now, 0));
-    FC_TRY(sort_pairs(c, c->sb[k], c->aux, slots, n, offsets, num_bags, &r.keys, &r.vals));
+    FC_TRY(sort_pairs(c, c->sb[k], c->aux, slots, n, offsets, num_bags, &r.keys, &r.vals, slots_out));
     FC_HIP(hipEventRecord(r.ev_sorted, c->aux));
     r.slots = slots; r.n = n; r.offsets = offsets; r.bags = num_bags;
     r.ticket = c->ticket;
@@ -527,7 +528,7 @@ static int bwd_run(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t n,
         ProfScope ps(prof, P_BWD_REDUCE, st);
         BwdMeta* bm = reinterpret_cast<BwdMeta*>(pmeta);
 #define FC_BWD(V, S) \
-        k_bwd_reduce<V, S><<<(unsigned)rblocks, rthreads, lds, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, part, bm)
+        k_bwd_reduce<V, S><<<(unsigned)rblocks, rthreads, lds + c->bwd_pad, st>>>(kin, vin, (int)n, (int)c->C, grad, c->cache, c->D, sh, lr, part, bm)
 #define FC_BWD_V(S) \
         switch (c->vec) { case 4: FC_BWD(4, S); break; case 2: FC_BWD(2, S); break; default: FC_BWD(1, S); break; }
         if (n == num_bags) { FC_BWD_V(true) } else { FC_BWD_V(false) }

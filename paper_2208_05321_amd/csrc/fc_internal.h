@@ -96,7 +96,8 @@ struct fc_cache {
     // the current one.  pst = the stream the cache_prepare / cache_prepare_next in progress enqueues on.
     hipStream_t pre = nullptr, pst = nullptr, last_pst = nullptr;
     hipEvent_t ev_s_now = nullptr, ev_pre_done = nullptr, ev_index_done = nullptr;
-    hipEvent_t ev_assign_done = nullptr;   // index half: every decision taken (all but the slot write-out): the early fetch may start
+    hipEvent_t ev_assign_done = nullptr;   // index half: every decision taken (all but the slot write-out)
+    hipEvent_t ev_emit_done = nullptr;     // index half: the missing rows and where their newest copies are: the early fetch may start
     hipEvent_t ev_quiesce = nullptr;       // transit marks dropped by dma_quiesce on another stream than the index stream
     hipStream_t quiesce_stream = nullptr;
     hipStream_t last_index_stream = nullptr;
@@ -119,6 +120,8 @@ struct fc_cache {
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
     bool fwd_sorted = true;         // one-lookup-per-bag batches: forward in slot order when the pairs are sorted ahead of time (tuning: FC_FWD_SORTED=0)
+    int fwd_pad = 0, bwd_pad = 0;   // experiment (FC_FWD_PAD_KB / FC_BWD_PAD_KB): LDS claimed per workgroup of forward / backward beyond what
+                                    // they use, which caps how many of their workgroups share a compute unit
     bool last_one_per_bag = false;  // the batch of the latest index half has that shape
     int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)
@@ -271,13 +274,16 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // entry points implemented across the sources
 int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
-                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots = nullptr);
+                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots = nullptr, bool defer_slots = false);
+int launch_slots_out(fc_cache* c, hipStream_t st, int32_t* slots, int64_t n);
 int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv);
 int prepare_impl(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
                  int64_t num_bags, int32_t* slots);
 int fwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, float* out);
 int dma_quiesce(fc_cache* c, hipStream_t st);
-int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags);
+// from_ranks: the slots are not written yet; the sort's first kernel derives them from the per-id ranks and writes them
+// to `slots_out` on its way (the slot write-out folded into the sort)
+int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags, int32_t* slots_out = nullptr);
 int ensure_rbuf(fc_cache* c, int64_t n);  // per-id rank buffer for batches of n ids
 int reserve_bwd(fc_cache* c, int64_t n);   // sort scratch of all three sets and the partial rows for batches of n lookups
 int bwd_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* offsets, int64_t num_bags,
@@ -307,12 +313,15 @@ uint64_t pool_published(fc_cache* c);
 enum SortSrc {
     SORT_SRC_PAIRS = 0,   // keys_in / vals_in as given
     SORT_SRC_SLOTS = 1,   // keys_in = slots of a batch (out-of-range -> sentinel `limit`, flag raised), value = bag of lookup i
-    SORT_SRC_COUNTS = 2   // keys_in = occurrence counts, key = limit - count (limit = largest count), value = i
+    SORT_SRC_COUNTS = 2,  // keys_in = occurrence counts, key = limit - count (limit = largest count), value = i
+    SORT_SRC_RANKS = 3    // keys_in = frequency ranks of a batch's ids: the first kernel looks their slots up in rank_slot and
+                          // writes them to slots_out; from then on as SORT_SRC_SLOTS with keys_in = slots_out
 };
 struct SortJob {
     int src = SORT_SRC_PAIRS;
     const int32_t* keys_in = nullptr; const int32_t* vals_in = nullptr;
     const int64_t* offsets = nullptr; int num_bags = 0;
+    const int32_t* rank_slot = nullptr; int32_t* slots_out = nullptr;     // SORT_SRC_RANKS
     int n = 0, limit = 0, bits = 1;
     uint32_t* flags = nullptr;                 // device word for EF_BAD_SLOT, may be null
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;   // n ints each

@@ -268,7 +268,7 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
                                                           int32_t* __restrict__ miss_ranks, int32_t* __restrict__ vrank,
                                                           int32_t* __restrict__ vslot, int32_t* rank_slot,
                                                           int32_t* slot_rank, int C, int transit_base,
-                                                          int transit_rows) {
+                                                          int transit_rows, int32_t* __restrict__ fill_src) {
     __shared__ int lds[RT_THREADS / 64];
     const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
     const uint4 u4 = ubits4[idx];
@@ -301,7 +301,10 @@ __global__ __launch_bounds__(RT_THREADS) void k_rank_emit(uint4* ubits4, uint4* 
             uint32_t word = mw[k];
             while (word) {
                 const int bit = __ffs(word) - 1;
-                miss_ranks[o++] = rank0 + k * 32 + bit;
+                const int rank = rank0 + k * 32 + bit;
+                // where the row's newest copy is: -1 the host table, <= -2 an evicted-row block (in transit)
+                if (fill_src) fill_src[o] = rank_slot[rank];
+                miss_ranks[o++] = rank;
                 word &= word - 1;
             }
         }
@@ -385,8 +388,7 @@ __global__ __launch_bounds__(FREE_THREADS) void k_free_count(const int32_t* __re
 
 __global__ __launch_bounds__(FREE_THREADS) void k_free_assign(int32_t* slot_rank, int C, const int32_t* __restrict__ tcount,
                                                               int M, const int32_t* __restrict__ miss_ranks,
-                                                              int32_t* __restrict__ fill_slots, int32_t* rank_slot,
-                                                              int32_t* __restrict__ fill_src) {
+                                                              int32_t* __restrict__ fill_slots, int32_t* rank_slot) {
     __shared__ int lds[FREE_THREADS / 64];
     int part = 0;
     for (int g = threadIdx.x; g < (int)blockIdx.x; g += FREE_THREADS) part += tcount[g];
@@ -404,7 +406,6 @@ __global__ __launch_bounds__(FREE_THREADS) void k_free_assign(int32_t* slot_rank
         const int r = miss_ranks[j];
         fill_slots[j] = s;
         slot_rank[s] = r;
-        if (fill_src) fill_src[j] = rank_slot[r];     // -1: host table; <= -2: evicted-row block (in transit)
         rank_slot[r] = s;
         ++j;
     }
@@ -636,9 +637,19 @@ static int wait_for_ticket(const volatile int32_t* ticket_word, int32_t ticket, 
 
 // Index half of Algorithm 1: every decision (unique rows, misses, victims, slot assignment, both maps, the slots
 // of the batch) and no row movement.  Fills *mv with what prepare_move has to do.
+int launch_slots_out(fc_cache* c, hipStream_t st, int32_t* slots, int64_t n) {
+    if (n > 0) {
+        ProfScope ps(c, P_SLOTS_OUT, st);
+        k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
+    }
+    FC_HIP(hipGetLastError());
+    return FC_OK;
+}
+
 // before_slots: an event the slot write-out (the first kernel that writes the caller's buffer) has to wait for.
+// defer_slots: leave the slot write-out and the ev_index_done record to the caller (who folds the write-out into the sort).
 int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* ids, int64_t n, const int64_t* offsets,
-                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots) {
+                  int64_t num_bags, int32_t* slots, MovePlan* mv, hipEvent_t before_slots, bool defer_slots) {
     const int64_t LIM = ((int64_t)1 << 31) - 65536;
     if (!c || n < 0 || num_bags < 0 || n >= LIM || num_bags >= LIM || !offsets || (n > 0 && (!ids || !slots)))
         return FC_ERR_INVALID_ARG;
@@ -701,8 +712,10 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
         k_rank_emit<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((uint4*)c->ubits, (uint4*)c->rbits, (uint4*)c->pbits, protect_prev, c->ctl,
                                                            c->moff, c->vtake, c->voff,
                                                            c->miss_ranks, c->vrank, c->vslot, c->rank_slot, c->slot_rank, (int)c->C,
-                                                           c->dirty_track ? -1 : transit_base, (int)c->staging_rows);
+                                                           c->dirty_track ? -1 : transit_base, (int)c->staging_rows,
+                                                           c->dma_evict ? c->fill_src : nullptr);
     }
+    FC_HIP(hipEventRecord(c->ev_emit_done, st));
     FC_HIP(hipGetLastError());
     // the planning kernel's decision
     HostCtl h;
@@ -724,19 +737,17 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
             }
             ProfScope ps(c, P_FREE_PICK, st);
             k_free_assign<<<tiles, FREE_THREADS, 0, st>>>(c->slot_rank, (int)c->C, c->tcount, (int)M, c->miss_ranks, c->fill_slots,
-                                                      c->rank_slot, c->dma_evict ? c->fill_src : nullptr);
+                                                      c->rank_slot);
         }
     }
     FC_HIP(hipEventRecord(c->ev_assign_done, st));
     // every row of the batch has its slot now: write the slots out (the caller then starts sorting them for the
     // backward pass on a library stream, where the sort runs while the missing rows cross the host link)
     if (before_slots) FC_HIP(hipStreamWaitEvent(st, before_slots, 0));
-    if (n > 0) {
-        ProfScope ps(c, P_SLOTS_OUT, st);
-        k_slots_out<<<(unsigned)cdiv(n, 256), 256, 0, st>>>(c->rbuf, c->rank_slot, slots, (int)n);
+    if (!defer_slots) {
+        FC_TRY(launch_slots_out(c, st, slots, n));
+        FC_HIP(hipEventRecord(c->ev_index_done, st));
     }
-    FC_HIP(hipGetLastError());
-    FC_HIP(hipEventRecord(c->ev_index_done, st));
     c->last_index_stream = st;
     c->aux = (st == c->pre && !lookahead) ? c->pre : c->pf;
     mv->valid = true; mv->M = M; mv->need = need; mv->buf = buf; mv->transit_base = transit_base;
@@ -755,7 +766,9 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
 // Row-movement half: evicted rows out (gather, then DMA block / kernel store / staged copy), missing rows in.
 int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     c->pst = st;
-    if (c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_index_done, 0));
+    // the lists this half reads are complete once the last decision is taken; the slot write-out (and, folded into it,
+    // the sort) is waited for by whoever hands the batch to the caller
+    if (c->last_index_stream != st) FC_HIP(hipStreamWaitEvent(st, c->ev_assign_done, 0));
     const int64_t M = mv.M;
     int64_t need = mv.need;                    // victims to write back
     const bool staged = (c->flags & FC_TRANSMIT_STAGED) != 0;

@@ -35,13 +35,28 @@ __device__ __forceinline__ int load_key(const int32_t* __restrict__ keys_in, int
 template <int SRC, int ITEMS>
 __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restrict__ keys_in, int n, int limit, int shift,
                                                           int radix_bits, int nblk, int32_t* __restrict__ ghist,
-                                                          uint32_t* flags) {
+                                                          uint32_t* flags, const int32_t* __restrict__ rank_slot,
+                                                          int32_t* __restrict__ slots_out) {
     __shared__ int h[1 << RS_MAX_BITS];
     const int radix = 1 << radix_bits, mask = radix - 1;
     const int tile0 = blockIdx.x * (RS_THREADS * ITEMS);
     // all of the tile's keys are requested before anything waits for one (a lane beyond n rereads the last key)
     int key[ITEMS];
     bool bad = false;
+    if (SRC == SORT_SRC_RANKS) {
+        // gpu_row_idx of every input id (Algorithm 1's last index_select), written out on the way to becoming sort keys
+        int r[ITEMS];
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) r[it] = keys_in[min(tile0 + it * RS_THREADS + (int)threadIdx.x, n - 1)];
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) key[it] = rank_slot[r[it]];
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int i = tile0 + it * RS_THREADS + (int)threadIdx.x;
+            if (i < n) slots_out[i] = key[it];
+            if ((unsigned)key[it] >= (unsigned)limit) { bad = true; key[it] = limit; }
+        }
+    } else
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it)
         key[it] = load_key<SRC>(keys_in, min(tile0 + it * RS_THREADS + (int)threadIdx.x, n - 1), limit, bad);
@@ -192,7 +207,17 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     const int nblk = (int)cdiv(j.n, RS_THREADS * ITEMS);
     {
         ProfScope ps(j.prof, P_SORT_HIST, st);
-        k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, j.flags);
+        k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, j.flags, j.rank_slot, j.slots_out);
+    }
+    if (SRC == SORT_SRC_RANKS) {        // the slots are written now: the rest of the pass reads them
+        ProfScope ps(j.prof, P_SORT_SCAN, st);
+        k_sort_scan<<<(unsigned)cdiv((int64_t)radix * 64, 256), 256, 0, st>>>(j.ghist, nblk, radix, j.dtot);
+    }
+    if (SRC == SORT_SRC_RANKS) {
+        ProfScope ps(j.prof, P_SORT_SCATTER, st);
+        k_sort_scatter<SORT_SRC_SLOTS, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(j.slots_out, vin, j.offsets, j.num_bags, j.n, j.limit, shift, rb,
+                                                                                     nblk, j.ghist, j.dtot, kout, vout);
+        return;
     }
     {
         ProfScope ps(j.prof, P_SORT_SCAN, st);
@@ -222,6 +247,7 @@ int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int
         const int shift = p * rb;
         if (p > 0 || j.src == SORT_SRC_PAIRS) launch_pass<SORT_SRC_PAIRS>(j, st, kin, vin, kout, vout, shift, rb);
         else if (j.src == SORT_SRC_SLOTS) launch_pass<SORT_SRC_SLOTS>(j, st, kin, vin, kout, vout, shift, rb);
+        else if (j.src == SORT_SRC_RANKS) launch_pass<SORT_SRC_RANKS>(j, st, kin, vin, kout, vout, shift, rb);
         else launch_pass<SORT_SRC_COUNTS>(j, st, kin, vin, kout, vout, shift, rb);
         kin = kout; vin = vout;
         if (kout == j.keysA) { kout = j.keysB; vout = j.valsB; } else { kout = j.keysA; vout = j.valsA; }

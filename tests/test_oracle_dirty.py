@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import Oracle
-from tests.alg1_arrayops import ArrayOpsCache
+from tests.alg1_bruteforce import BruteForceCache
 from workloads import table_values
 
 
@@ -72,7 +72,7 @@ def pin_values_identical(mk):
 
 
 def pin_writeback_set_against_model(mk):
-    """The write-back set predicted without the oracle: Algorithm 1 in array operations gives the victims; a Python set
+    """The write-back set predicted without the oracle: a brute-force statement of Algorithm 1 (Python sets) gives the victims; a Python set
     of rows updated since they were loaded says which of them are dirty."""
     for seed in range(3):
         rng = np.random.default_rng(90 + seed)
@@ -81,7 +81,7 @@ def pin_writeback_set_against_model(mk):
         ha = table_values(seed, np.arange(N), D).copy()
         warm = bool(seed % 2)
         o = mk(fr, ha, C, warm, True)
-        ref = ArrayOpsCache(fr, ha.copy(), C, warm=warm)
+        ref = BruteForceCache(fr, ha.copy(), C, warm=warm)
         updated = set()
         for t in range(50):
             k = int(rng.integers(1, C + 1))

@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from oracle.wrapper import Oracle, OracleError, _load, _SRC
-from tests.alg1_arrayops import ArrayOpsCache
+from tests.alg1_bruteforce import BruteForceCache
 from tests.test_oracle_dirty import DIRTY_PINS
 from workloads import table_values
 
@@ -40,7 +40,7 @@ def battery(lib):
             assert list(L["miss_ranks"]) == b["miss_ranks"] and list(L["evict_ranks"]) == b["evict_ranks"]
             assert list(L["fill_slots"]) == b["fill_slots"] and list(o.slot_rank) == b["slot_rank_after"]
             assert list(slots) == b["slots"] and s["n_hit_ids"] == b["n_hit_ids"] and s["n_unique"] == b["n_unique"]
-    # P1 array-op Algorithm 1 (plain and look-ahead), with row values travelling through evictions
+    # P1 brute-force Algorithm 1 (plain and look-ahead), with row values travelling through evictions
     for seed in range(4):
         rng = np.random.default_rng(seed)
         N, C, D = 40, 7, 3
@@ -48,7 +48,7 @@ def battery(lib):
         ha = table_values(seed, np.arange(N), D).copy()
         hb = ha.copy()
         o = mk(fr, ha, C, bool(seed % 2))
-        ref = ArrayOpsCache(fr, hb, C, warm=bool(seed % 2))
+        ref = BruteForceCache(fr, hb, C, warm=bool(seed % 2))
         prev = None
         for t in range(30):
             k = int(rng.integers(1, C // 2 + 1))

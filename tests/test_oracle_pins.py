@@ -1,7 +1,7 @@
 """Pins for the CPU oracle (oracle/fc_oracle.c): everything here runs without a GPU.
 
 P0  hand-worked traces of Algorithm 1 (tests/golden/alg1_handworked.json)
-P1  array-op rendering of Algorithm 1 (tests/alg1_arrayops.py) on tiny tables, random traces
+P1  brute-force statement of Algorithm 1 with Python sets and dicts (tests/alg1_bruteforce.py) on tiny tables, random traces
 P2  cache transparency: flushed table == EmbeddingBag-sum + SGD on the whole table, no cache
     (Section 2.2: updates are synchronous, so the cache must be invisible)
 P3  closed form for config 1 (all-ones gradient, one id per bag)
@@ -16,7 +16,7 @@ import pytest
 import torch
 
 from oracle import Oracle, OracleError
-from tests.alg1_arrayops import ArrayOpsCache
+from tests.alg1_bruteforce import BruteForceCache
 from workloads import make_workload, table_values
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -77,7 +77,7 @@ def test_against_array_ops_algorithm1(seed):
     host_a = rand_table(N, D, seed)
     host_b = host_a.copy()
     o = Oracle(fr, host_a, C, warm=warm)
-    ref = ArrayOpsCache(fr, host_b, C, warm=warm)
+    ref = BruteForceCache(fr, host_b, C, warm=warm)
     for t in range(40):
         kind = t % 5
         if kind == 0:      # exactly C distinct rows: the whole cache is needed
@@ -412,7 +412,7 @@ def test_lookahead_against_array_ops_algorithm1(seed):
     host_a = rand_table(N, 2, seed)
     host_b = host_a.copy()
     o = Oracle(fr, host_a, C, warm=bool(seed % 2))
-    ref = ArrayOpsCache(fr, host_b, C, warm=bool(seed % 2))
+    ref = BruteForceCache(fr, host_b, C, warm=bool(seed % 2))
     prev = None
     for t in range(40):
         k = int(rng.integers(1, C // 2 + 1))          # two batches always fit together

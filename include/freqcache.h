@@ -59,7 +59,8 @@ enum {
     FC_ERR_HIP = -8,                 /* a HIP runtime call failed, or no usable device            */
     FC_ERR_NOT_PINNED = -9,          /* host_weight given but not page-locked, GPU-mapped memory  */
     FC_ERR_BAD_SLOT = -10,           /* a slot index outside [0, cache_rows) reached fwd / bwd     */
-    FC_ERR_SCRATCH_EXCEEDED = -11    /* embedding_bag_bwd_sgd_noalloc: the batch needs more than its fixed scratch */
+    FC_ERR_SCRATCH_EXCEEDED = -11,   /* embedding_bag_bwd_sgd_noalloc: the batch needs more than its fixed scratch */
+    FC_ERR_COUNT_OVERFLOW = -12      /* freq_add: more than 2^31 - 1 ids in all would overflow the 32-bit counters */
 };
 
 /* Limits of embedding_bag_bwd_sgd_noalloc (below). */
@@ -273,7 +274,8 @@ typedef struct fc_freq fc_freq; /* opaque accumulator of per-id occurrence count
 int freq_create(int64_t num_rows, void* hip_stream, fc_freq** out);
 /* counts[id] += 1 for each of the n ids (int64, device memory): one scan step over the dataset, or over a sample of
  * it when the dataset is too large (Section 4.2).  Asynchronous; ids outside [0, num_rows) are skipped and make
- * freq_build fail with FC_ERR_ID_OUT_OF_RANGE. */
+ * freq_build fail with FC_ERR_ID_OUT_OF_RANGE.  The counters are 32 bits wide: once the ids of all calls together would
+ * exceed 2^31 - 1 the call returns FC_ERR_COUNT_OVERFLOW and counts nothing (sample the dataset instead). */
 int freq_add(fc_freq* f, const int64_t* ids_dev, int64_t n);
 /* Order the rows from high to low occurrence count, equal counts by lower id:
  *   freq_rank_host[id] = position of id in that order (the idx_map cache_create takes), int32[num_rows];

@@ -36,8 +36,12 @@ def _load(path: str | None = None):
     global _lib
     if _lib is None or path is not None:
         if path is None:
-            build()
-        L = ctypes.CDLL(path or _LIB)
+            path_env = os.environ.get("FC_ORACLE_LIB")      # another build of fc_oracle.c (the sanitizer run of tests/)
+            if not path_env:
+                build()
+        else:
+            path_env = None
+        L = ctypes.CDLL(path or path_env or _LIB)
         vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
         L.fco_create.argtypes = [i64, i32, i64, vp, vp, i32, ctypes.POINTER(vp)]
         L.fco_create.restype = ctypes.c_int

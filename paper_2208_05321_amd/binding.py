@@ -20,7 +20,7 @@ FC_INPUTS_READY = 32
 ERR_NAMES = {
     0: "OK", -1: "INVALID_ARG", -2: "ID_OUT_OF_RANGE", -3: "BAD_OFFSETS", -4: "BATCH_EXCEEDS_CACHE",
     -5: "NOT_PERMUTATION", -6: "OOM_DEVICE", -7: "OOM_PINNED", -8: "HIP", -9: "NOT_PINNED", -10: "BAD_SLOT",
-    -11: "SCRATCH_EXCEEDED",
+    -11: "SCRATCH_EXCEEDED", -12: "COUNT_OVERFLOW",
 }
 NOALLOC_MAX_IDS = 524288
 STAT_FIELDS = ("n_ids", "n_unique", "n_hit_unique", "n_hit_ids", "n_miss", "n_evict", "bytes_h2d", "bytes_d2h")

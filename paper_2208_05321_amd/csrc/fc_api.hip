@@ -686,6 +686,7 @@ const char* cache_strerror(int code) {
         case FC_ERR_HIP: return "HIP runtime error or no usable GPU";
         case FC_ERR_NOT_PINNED: return "host_weight is not pinned, GPU-mapped memory";
         case FC_ERR_BAD_SLOT: return "slot index outside [0, cache_rows)";
+        case FC_ERR_COUNT_OVERFLOW: return "freq_add: more ids than the 32-bit counters can hold";
         case FC_ERR_SCRATCH_EXCEEDED: return "batch too large for the fixed scratch of embedding_bag_bwd_sgd_noalloc";
         default: return "unknown error";
     }

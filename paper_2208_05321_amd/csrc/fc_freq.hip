@@ -3,6 +3,8 @@
 // re-order the embedding table accordingly.
 #include "fc_internal.h"
 
+#include <limits.h>
+
 #include <new>
 #include <vector>
 
@@ -11,6 +13,7 @@ struct fc_freq {
     int device = 0;
     hipStream_t stream = nullptr;
     int32_t* counts = nullptr;     // [N]
+    int64_t total = 0;             // ids counted so far: no single counter can exceed it
     uint32_t* flags = nullptr;     // EF_ID_RANGE
     int32_t* maxc = nullptr;
 };
@@ -180,6 +183,10 @@ int freq_create(int64_t num_rows, void* hip_stream, fc_freq** out) {
 int freq_add(fc_freq* f, const int64_t* ids_dev, int64_t n) {
     if (!f || n < 0 || (n > 0 && !ids_dev)) return FC_ERR_INVALID_ARG;
     if (n == 0) return FC_OK;
+    // counters are 32 bits wide: an id that occurred more than 2^31 - 1 times would wrap around unnoticed, so the
+    // accumulator takes at most that many ids in all (larger datasets are sampled, as Section 4.2 suggests)
+    if (f->total + n > (int64_t)INT32_MAX) return FC_ERR_COUNT_OVERFLOW;
+    f->total += n;
     FC_HIP(hipSetDevice(f->device));
     k_freq_count<<<(unsigned)cdiv(n, FQ_THREADS * FQ_ITEMS), FQ_THREADS, 0, f->stream>>>(ids_dev, n, f->N, f->counts, f->flags);
     FC_HIP(hipGetLastError());

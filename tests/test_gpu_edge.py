@@ -373,7 +373,7 @@ def test_profile_timeline_file(torch_cuda, tmp_path, monkeypatch):
     cache_profile_get are the sums of those spans."""
     torch = torch_cuda
     from paper_2208_05321_amd import FreqCache
-    from paper_2208_05321_amd.timeline import load_first_collection
+    from tests.timeline_file import load_first_collection
     w = make_workload("c1")
     dev = torch.device("cuda:0")
     path = tmp_path / "timeline.txt"

@@ -472,3 +472,34 @@ def test_lookahead_fails_cleanly_when_two_batches_do_not_fit():
     assert e.value.name == "BATCH_EXCEEDS_CACHE"
     assert np.array_equal(sr, o.slot_rank) and np.array_equal(rs, o.rank_slot)
     o.prepare(b, one_hot_offsets(8))                  # the plain call fits
+
+
+def test_bag_sum_on_supplied_rows_is_the_forward_definition():
+    """oracle.bag_sum (the forward's arithmetic applied to rows the caller supplies; the GPU tests use it to check the
+    forward kernel bit for bit on the GPU's own rows): against a direct fp32 loop, torch's embedding_bag in fp64, and
+    Oracle.embedding_bag_fwd on the oracle's own cached rows."""
+    import torch
+    from oracle import bag_sum
+    rng = np.random.default_rng(5)
+    C, D = 37, 6
+    rows = rng.standard_normal((C, D)).astype(np.float32)
+    sizes = rng.integers(0, 5, size=23)                     # empty bags included
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    slots = rng.integers(0, C, size=int(offsets[-1])).astype(np.int32)
+    got = bag_sum(rows, slots, offsets)
+    ref = np.zeros((len(sizes), D), dtype=np.float32)
+    for b in range(len(sizes)):
+        for i in range(offsets[b], offsets[b + 1]):
+            ref[b] = ref[b] + rows[slots[i]]                # one row after the other, fp32
+    assert np.array_equal(got, ref)
+    t = torch.nn.functional.embedding_bag(torch.from_numpy(slots.astype(np.int64)), torch.from_numpy(rows.astype(np.float64)),
+                                          torch.from_numpy(offsets[:-1]), mode="sum")
+    assert np.allclose(got, t.numpy(), rtol=1e-6, atol=1e-6)
+    assert np.array_equal(got[sizes == 0], np.zeros((int((sizes == 0).sum()), D), dtype=np.float32))
+    # same routine as the oracle's forward on its own rows
+    N = 200
+    fr = rng.permutation(N).astype(np.int32)
+    host = rng.standard_normal((N, D)).astype(np.float32)
+    o = Oracle(fr, host, C, warm=True)
+    assert np.array_equal(o.embedding_bag_fwd(slots, offsets), bag_sum(o.cache, slots, offsets))
+    o.close()

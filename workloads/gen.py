@@ -50,8 +50,10 @@ def _native():
     global _lib
     if _lib is None:
         try:
-            build_native()
-            lib = ctypes.CDLL(_LIB_PATH)
+            alt = os.environ.get("FC_FILL_LIB")               # another build of fill.c (the sanitizer run of tests/)
+            if not alt:
+                build_native()
+            lib = ctypes.CDLL(alt or _LIB_PATH)
             lib.fc_fill_table.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64]
             lib.fc_fill_table.restype = None
             lib.fc_fill_normal.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64]
@@ -245,19 +247,25 @@ class Workload:
                 score[perm[a:b]] = p / F
         else:
             counts = np.zeros(self.num_rows, dtype=np.int64)
-            left, t = self.warm_samples, 0
-            while left > 0:
-                s = min(left, 1 << 18)
-                ids, _ = self._draw(s, seed=self.seed + 7919, t=t, shift_batch=0)
+            for ids in self.warmup_trace():
                 counts += np.bincount(ids, minlength=self.num_rows)
-                left -= s
-                t += 1
             score = counts.astype(np.float64)
         order = np.argsort(-score, kind="stable")               # rank -> id, ties by lower id
         self.inv_rank = order.astype(np.int32)
         self.freq_rank = np.empty(self.num_rows, dtype=np.int32)
         self.freq_rank[order] = np.arange(self.num_rows, dtype=np.int32)
         return self
+
+    def warmup_trace(self):
+        """The seeded warm-up trace empirical ranks are counted on (Section 4.2: id frequencies from a scan of the data, or
+        of a sample of it), in chunks of ids; a different seed than the batches of the run."""
+        left, t = self.warm_samples, 0
+        while left > 0:
+            s = min(left, 1 << 18)
+            ids, _ = self._draw(s, seed=self.seed + 7919, t=t, shift_batch=0)
+            yield ids
+            left -= s
+            t += 1
 
     # ---- per-batch inputs ---------------------------------------------------
     def _draw(self, samples: int, seed: int, t: int, shift_batch: int):

@@ -92,6 +92,14 @@ enum {
                                caller's stream at all (only the slot write-out and the sort still wait for the backward pass
                                that last read those buffers), which puts the planned batch's index decisions and row fetch a
                                whole step ahead of cache_advance.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
+    FC_MISS_DMA = 64,       /* cache_plan_next only, with FC_EVICT_DMA or the default transmitter: the planned batch's missing rows
+                               cross the link the way the paper's transmitter moves them (Section 4.3), pipelined: their list
+                               is copied to the host, library-owned host threads (FC_GATHER_THREADS, default 6) gather the
+                               rows from the host table into a pinned block chunk by chunk, and each chunk goes into the
+                               arrival block in HBM by hipMemcpyAsync (DMA engine) on the fetch stream; no compute unit reads
+                               host memory.  cache_advance waits on the host until the last chunk has been handed over.
+                               Memory: two more pinned blocks of staging_rows * dim * 4 bytes.  Results are identical.
+                               Ignored with FC_DIRTY_TRACK. */
     FC_DIRTY_TRACK = 16     /* Variant beyond the paper (Algorithm 1 always calls move_to_cpu): a resident row is
                                dirty once embedding_bag_bwd_sgd has updated it since it was loaded; only dirty
                                victims are written back, clean ones are dropped (their copy in the host table is
@@ -122,7 +130,7 @@ enum {
  *                   staging_rows * dim * 4 bytes: one in HBM by default; with FC_TRANSMIT_STAGED two in
  *                   HBM and one pinned; with FC_EVICT_DMA four in HBM and four pinned; cache_plan_next
  *                   adds two in HBM on first use.
- *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK, FC_INPUTS_READY.
+ *   flags           any of FC_WARM, FC_TRANSMIT_STAGED, FC_EVICT_DMA, FC_NO_PRESORT, FC_DIRTY_TRACK, FC_INPUTS_READY, FC_MISS_DMA.
  *   hip_stream      hipStream_t on which all per-batch work is enqueued (NULL = default stream).
  *   out             receives the handle.
  * Errors: INVALID_ARG, NOT_PERMUTATION, NOT_PINNED, OOM_DEVICE, OOM_PINNED, HIP.  Synchronous (it also runs a few

@@ -16,6 +16,7 @@ FC_EVICT_DMA = 4
 FC_NO_PRESORT = 8
 FC_DIRTY_TRACK = 16
 FC_INPUTS_READY = 32
+FC_MISS_DMA = 64
 
 ERR_NAMES = {
     0: "OK", -1: "INVALID_ARG", -2: "ID_OUT_OF_RANGE", -3: "BAD_OFFSETS", -4: "BATCH_EXCEEDS_CACHE",
@@ -112,7 +113,7 @@ class FreqCache:
     def __init__(self, num_rows: int, dim: int, cache_rows: int, freq_rank: np.ndarray, host_weight=None,
                  staging_rows: int = 0, warm: bool = False, staged: bool = False, stream=None,
                  dma_evict: bool = False, presort: bool = True, dirty_tracking: bool = False,
-                 inputs_ready: bool = False):
+                 inputs_ready: bool = False, miss_dma: bool = False):
         import torch
 
         if not torch.cuda.is_available():
@@ -128,7 +129,7 @@ class FreqCache:
             assert host_weight.dtype == torch.float32 and host_weight.is_contiguous()
             assert host_weight.numel() == self.num_rows * self.dim
         self.stream = stream if stream is not None else torch.cuda.current_stream()
-        flags = (FC_WARM if warm else 0) | (FC_TRANSMIT_STAGED if staged else 0) | (FC_EVICT_DMA if dma_evict else 0) | (0 if presort else FC_NO_PRESORT) | (FC_DIRTY_TRACK if dirty_tracking else 0) | (FC_INPUTS_READY if inputs_ready else 0)
+        flags = (FC_WARM if warm else 0) | (FC_TRANSMIT_STAGED if staged else 0) | (FC_EVICT_DMA if dma_evict else 0) | (0 if presort else FC_NO_PRESORT) | (FC_DIRTY_TRACK if dirty_tracking else 0) | (FC_INPUTS_READY if inputs_ready else 0) | (FC_MISS_DMA if miss_dma else 0)
         h = ctypes.c_void_p()
         rc = self._L.cache_create(self.num_rows, self.dim, self.cache_rows, fr.ctypes.data, _ptr(host_weight),
                                   int(staging_rows), flags, ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfreqcache.so")
-SOURCES = ["fc_api.hip", "fc_prepare.hip", "fc_rows.hip", "fc_embedding.hip", "fc_sort.hip", "fc_worker.hip", "fc_freq.hip"]
+SOURCES = ["fc_api.hip", "fc_prepare.hip", "fc_rows.hip", "fc_embedding.hip", "fc_sort.hip", "fc_worker.hip", "fc_gather.hip", "fc_freq.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fopenmp", "-pthread",
     "-ffp-contract=off",                                   # SGD step: rounded product, then subtract

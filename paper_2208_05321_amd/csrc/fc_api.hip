@@ -82,6 +82,8 @@ __global__ void k_set_ctl(Ctl* ctl, int nfree) {
 
 static int reset_state(fc_cache* c, bool warm) {
     hipStream_t st = c->stream;
+    (void)gather_wait(c);
+    c->gather_pending = false;
     for (hipStream_t x : {c->pre, c->pf, c->side}) if (x) FC_HIP(hipStreamSynchronize(x));
     c->next_pending = false; c->last_pst = c->stream;
     c->planned.valid = false; c->last_index_stream = nullptr; c->move_stream[0] = c->move_stream[1] = nullptr; c->pf_dep = nullptr;
@@ -112,8 +114,14 @@ static void destroy(fc_cache* c) {
     if (c->tune_early && getenv("FC_TUNE_REPORT"))
         fprintf(stderr, "freqcache: early-fetch workgroups settled at %d (fetch / copy ratio %.3f)\n", c->fill_blocks_early, c->tune_ratio);
     (void)hipSetDevice(c->device);
+    (void)gather_wait(c);              // no gather thread is about to enqueue a copy
     if (c->stream || c->side) (void)hipDeviceSynchronize();
+    gather_destroy(c);
     pool_destroy(c);
+    for (int k = 0; k < 2; ++k) {
+        for (void* p : {(void*)c->arrive_pin[k], (void*)c->miss_pin[k], (void*)c->src_pin[k]}) if (p) (void)hipHostFree(p);
+        if (c->ev_list[k]) (void)hipEventDestroy(c->ev_list[k]);
+    }
     for (int b = 0; b < DMA_BLOCKS; ++b) {
         if (c->blk_pin[b]) (void)hipHostFree(c->blk_pin[b]);
         if (c->vrank_pin[b]) (void)hipHostFree(c->vrank_pin[b]);
@@ -329,6 +337,20 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
         if (const char* e = getenv("FC_SCATTER_THREADS")) { const int v = atoi(e); if (v >= 1 && v <= 64) threads = v; }
         FC_TRY(pool_create(c, threads));
     }
+    c->miss_dma = (flags & FC_MISS_DMA) != 0 && !c->dirty_track;
+    if (c->miss_dma) {
+        for (int k = 0; k < 2; ++k) {
+            if (hipHostMalloc((void**)&c->arrive_pin[k], (size_t)staging_rows * D * 4, hipHostMallocDefault) != hipSuccess ||
+                hipHostMalloc((void**)&c->miss_pin[k], (size_t)staging_rows * 4, hipHostMallocDefault) != hipSuccess ||
+                hipHostMalloc((void**)&c->src_pin[k], (size_t)staging_rows * 4, hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError(); return FC_ERR_OOM_PINNED;
+            }
+            FC_HIP(hipEventCreateWithFlags(&c->ev_list[k], hipEventDisableTiming));
+        }
+        int threads = 6;
+        if (const char* e = getenv("FC_GATHER_THREADS")) { const int v = atoi(e); if (v >= 1 && v <= 64) threads = v; }
+        FC_TRY(gather_create(c, threads));
+    }
     return reset_state(c, (flags & FC_WARM) != 0);
 }
 
@@ -378,6 +400,14 @@ static bool ensure_arrival_block(fc_cache* c, int k) {
 static int fetch_early(fc_cache* c, int64_t M) {
     const int k = c->lset;
     if (!ensure_arrival_block(c, k)) return FC_OK;   // no room for the block: the rows are fetched at cache_advance instead
+    if (c->miss_dma) {
+        // host threads gather the rows, the DMA engine carries them; ev_arrive[k] is recorded by the thread that hands over
+        // the last chunk, and cache_advance waits (on the host) for that record before it makes its stream wait for it
+        FC_TRY(gather_start(c, M));
+        c->gather_pending = true;
+        c->planned.arrived = true;
+        return FC_OK;
+    }
     if (c->tune_early) tune_fetch_grid(c, k);
     FC_HIP(hipStreamWaitEvent(c->pf, c->ev_emit_done, 0));       // which rows are missing and where their newest copies are
     if (c->pf_dep) FC_HIP(hipStreamWaitEvent(c->pf, c->pf_dep, 0));
@@ -418,8 +448,8 @@ int cache_create(int64_t num_rows, int32_t dim, int64_t cache_rows, const int32_
     if (!out) return FC_ERR_INVALID_ARG;
     *out = nullptr;
     if (!freq_rank_host || num_rows <= 0 || num_rows >= LIM || dim <= 0 || dim > 1024 || cache_rows <= 0 || cache_rows > num_rows ||
-        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT | FC_DIRTY_TRACK | FC_INPUTS_READY)) ||
-        ((flags & FC_TRANSMIT_STAGED) && (flags & FC_EVICT_DMA)))
+        staging_rows < 0 || (flags & ~(FC_WARM | FC_TRANSMIT_STAGED | FC_EVICT_DMA | FC_NO_PRESORT | FC_DIRTY_TRACK | FC_INPUTS_READY | FC_MISS_DMA)) ||
+        ((flags & FC_TRANSMIT_STAGED) && (flags & (FC_EVICT_DMA | FC_MISS_DMA))))
         return FC_ERR_INVALID_ARG;
     if ((flags & FC_WARM) && !host_weight) return FC_ERR_INVALID_ARG;   // nothing to warm up from yet
     {   // idx_map must be a permutation: the host table is the original table re-ordered (Section 4.2)

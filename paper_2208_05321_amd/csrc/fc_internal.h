@@ -60,6 +60,7 @@ enum ProfItem {
 struct ProfSpan { int item; hipEvent_t a, b; };
 
 struct ScatterPool;   // host threads that scatter evicted-row blocks into the host table (fc_worker.hip)
+struct GatherPool;    // host threads that gather missing rows into a pinned block for the DMA miss path (fc_gather.hip)
 
 // Scratch of one radix sort of a batch's (slot, bag) pairs, and the record of a sort started ahead of time.
 struct SortBufs {
@@ -186,6 +187,15 @@ struct fc_cache {
     int64_t blk_rows[fc::DMA_BLOCKS] = {};        // rows whose transit marks are still set, per block
     hipEvent_t ev_d2h[fc::DMA_BLOCKS] = {};
     hipEvent_t pf_dep = nullptr;                  // what the next early fetch of missing rows has to wait for
+    // DMA miss path (FC_MISS_DMA): cache_plan_next's missing rows are gathered by host threads into a pinned block and
+    // copied into the arrival block by hipMemcpyAsync on the fetch stream, instead of being read by a kernel.
+    bool miss_dma = false;
+    fc::GatherPool* gpool = nullptr;
+    float* arrive_pin[2] = {nullptr, nullptr};    // [staging_rows][D], pinned
+    int32_t* miss_pin[2] = {nullptr, nullptr};    // [staging_rows] pinned copies of the missing ranks
+    int32_t* src_pin[2] = {nullptr, nullptr};     // ... and of where each row's newest copy is (-1: host table)
+    hipEvent_t ev_list[2] = {nullptr, nullptr};   // those copies have landed
+    bool gather_pending = false;                  // a job was started for the planned batch
     // The early fetch (zero-copy reads) and the evicted-row block copy (DMA writes) share the host link all the time in
     // the pipelined schedule; how they split it depends on the fetch's workgroup count, and a step gets longer, not
     // shorter, once the block copy is the slower one (more fetch workgroups also slow the index kernels of the batch
@@ -300,7 +310,15 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
 int launch_flush_rows(fc_cache* c, hipStream_t s);   // FC_DIRTY_TRACK: dirty rows only
 // miss fill that honours transit marks: row j comes from the host table or from a device-side evicted-row block
 // dst == nullptr: into the cache slots fill_slots[j]; else into row j of the block dst (of dst_rows rows)
-int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst = nullptr, int64_t dst_rows = 0, int max_blocks = 0);
+// only_transit: rows whose newest copy is in the host table are skipped (the DMA miss path has brought them)
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst = nullptr, int64_t dst_rows = 0, int max_blocks = 0,
+                     bool only_transit = false);
+
+// gather pool of the DMA miss path (fc_gather.hip)
+int gather_create(fc_cache* c, int threads);
+void gather_destroy(fc_cache* c);
+int gather_start(fc_cache* c, int64_t M);
+int gather_wait(fc_cache* c);
 
 // scatter pool (fc_worker.hip)
 int pool_create(fc_cache* c, int threads);

@@ -801,6 +801,10 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
     // victims need not wait for them; a kernel-store evict reuses the block buffer from its start and has to.
     bool arrival_waited = !mv.arrived;
     bool dma_path = false;
+    // DMA miss path: ev_arrive of this list set is recorded by a gather thread once it has handed the last chunk to the
+    // DMA engine; the host waits here until that has happened (the GPU meanwhile works through the current batch)
+    const bool via_dma = mv.arrived && c->gather_pending;
+    if (via_dma) { FC_TRY(gather_wait(c)); c->gather_pending = false; }
     if (need > 0) {
         if (staged) FC_TRY(evict_staged(c, need, c->list_pin + c->C));
         else if (c->dma_evict && mv.need <= c->staging_rows) { FC_TRY(evict_dma(c, need, mv.buf)); dma_path = true; }
@@ -819,7 +823,12 @@ int prepare_move(fc_cache* c, hipStream_t st, const MovePlan& mv) {
         }
         if (!arrival_waited) FC_HIP(hipStreamWaitEvent(st, c->ev_arrive[c->lset], 0));
         if (staged) FC_TRY(fill_staged(c, M, c->list_pin));
-        else if (mv.arrived) FC_TRY(launch_copy_rows(c, st, P_ROWS_IN, c->cache, c->fill_slots, c->C, c->arrive[c->lset], nullptr, c->staging_rows, M, 1 << 20));
+        else if (mv.arrived) {
+            FC_TRY(launch_copy_rows(c, st, P_ROWS_IN, c->cache, c->fill_slots, c->C, c->arrive[c->lset], nullptr, c->staging_rows, M, 1 << 20));
+            // DMA miss path: rows in transit did not come over the link; their newest copies are in evicted-row blocks
+            // gathered by earlier batches (this stream has run those gathers)
+            if (via_dma && c->dma_evict) FC_TRY(launch_fill_rows(c, st, M, nullptr, 0, 0, true));
+        }
         else if (c->dma_evict) FC_TRY(launch_fill_rows(c, st, M));
         else FC_TRY(launch_copy_rows(c, st, P_MISS_FILL, c->cache, c->fill_slots, c->C, c->host_dev, c->miss_ranks, c->N, M, c->fill_blocks));
     }

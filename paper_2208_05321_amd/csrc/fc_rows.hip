@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, co
                                                    unsigned C, const float* __restrict__ host,
                                                    const int32_t* __restrict__ miss_ranks, unsigned N,
                                                    const float* __restrict__ blocks, const int32_t* __restrict__ fill_src,
-                                                   unsigned block_rows, int rows, int D, int lpr_shift) {
+                                                   unsigned block_rows, int rows, int D, int lpr_shift, int only_transit) {
     using V = typename Vec<VEC>::T;
     const int lpr = 1 << lpr_shift;
     const int gpb = blockDim.x >> lpr_shift;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void k_fill_rows(float* __restrict__ cache, co
         if (code <= -2) {
             const unsigned k = (unsigned)(-2 - code);
             if (k < block_rows) srow = blocks + (size_t)k * D;
-        } else if ((unsigned)r < N) {
+        } else if (!only_transit && (unsigned)r < N) {
             srow = host + (size_t)r * D;
         }
         if (srow && (unsigned)di < C) {          // never false for lists this library builds
@@ -126,7 +126,7 @@ int launch_copy_rows(fc_cache* c, hipStream_t s, int prof_item, float* dst, cons
     return FC_OK;
 }
 
-int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst, int64_t dst_rows, int max_blocks) {
+int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst, int64_t dst_rows, int max_blocks, bool only_transit) {
     if (rows <= 0) return FC_OK;
     const int sh = shift_of(c->lpr);
     const int gpb = 256 >> sh;
@@ -137,7 +137,7 @@ int launch_fill_rows(fc_cache* c, hipStream_t s, int64_t rows, float* dst, int64
 #define FC_FILL(V) \
     k_fill_rows<V><<<(unsigned)blocks, 256, 0, s>>>(dst ? dst : c->cache, dst ? nullptr : c->fill_slots, (unsigned)(dst ? dst_rows : c->C), \
                                                     c->host_dev, c->miss_ranks, (unsigned)c->N, \
-                                                    c->stage_dev, c->fill_src, (unsigned)(DMA_BLOCKS * c->staging_rows), (int)rows, c->D, sh)
+                                                    c->stage_dev, c->fill_src, (unsigned)(DMA_BLOCKS * c->staging_rows), (int)rows, c->D, sh, only_transit ? 1 : 0)
     switch (c->vec) { case 4: FC_FILL(4); break; case 2: FC_FILL(2); break; default: FC_FILL(1); break; }
 #undef FC_FILL
     FC_HIP(hipGetLastError());

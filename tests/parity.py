@@ -315,7 +315,7 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
 
 
 def run_parity_planned(w, batches, warm=True, dma_evict=True, staging_rows=0, free_running=False, plan_first=False,
-                       dirty_tracking=False, forward_only=lambda t: False, log=None, inputs_ready=False):
+                       dirty_tracking=False, forward_only=lambda t: False, log=None, inputs_ready=False, miss_dma=False):
     """cache_plan_next: the index half of the next batch's prepare runs beside the current batch's forward / backward,
     rows move at cache_advance.  Same policy as plain cache_prepare, so the oracle is simply driven in program order.
     batches: a count (the first ones) or a list of batch numbers, as for run_parity."""
@@ -325,7 +325,7 @@ def run_parity_planned(w, batches, warm=True, dma_evict=True, staging_rows=0, fr
 
     dev = torch.device("cuda:0")
     gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking, inputs_ready=inputs_ready)
+                    warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking, inputs_ready=inputs_ready, miss_dma=miss_dma)
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()

@@ -48,7 +48,7 @@ def test_host_side_validation_needs_no_gpu(lib):
     assert lib.cache_create(10, 4, 0, fr.ctypes.data, None, 0, 0, None, ctypes.byref(h)) == -1      # cache_rows = 0
     assert lib.cache_create(10, 4, 11, fr.ctypes.data, None, 0, 0, None, ctypes.byref(h)) == -1     # > num_rows
     assert lib.cache_create(10, 4, 3, None, None, 0, 0, None, ctypes.byref(h)) == -1
-    assert lib.cache_create(10, 4, 3, fr.ctypes.data, None, 0, 64, None, ctypes.byref(h)) == -1     # unknown flag
+    assert lib.cache_create(10, 4, 3, fr.ctypes.data, None, 0, 1024, None, ctypes.byref(h)) == -1   # unknown flag
     bad = fr.copy()
     bad[0] = 1
     assert lib.cache_create(10, 4, 3, bad.ctypes.data, None, 0, 0, None, ctypes.byref(h)) == -5

@@ -149,6 +149,31 @@ def test_planned_prepare(torch_cuda, name, scale, ratio, dma, free, ready):
     run_parity_planned(w, 6, warm=True, dma_evict=dma, free_running=free, plan_first=True, inputs_ready=ready)
 
 
+@pytest.mark.parametrize("name,scale,ratio,dma,free,ready", [
+    ("c2", 0.1, 0.015, True, False, False), ("c2", 0.2, 0.015, True, True, True), ("c2", 0.2, 0.015, False, True, False),
+    ("c5", 0.05, 0.015, True, True, True), ("c4", 0.02, 0.03, True, True, True),
+])
+def test_planned_prepare_dma_miss_path(torch_cuda, name, scale, ratio, dma, free, ready):
+    """FC_MISS_DMA: the planned batch's missing rows are gathered by host threads and cross the link by hipMemcpyAsync
+    (the block transmitter of Section 4.3 for the host -> device direction); rows in transit come from the evicted-row
+    blocks at cache_advance.  Identical results, with and without the DMA evict transmitter."""
+    w = make_workload(name, scale=scale, cache_ratio=ratio)
+    run_parity_planned(w, 16 if free else 8, warm=True, dma_evict=dma, free_running=free, inputs_ready=ready, miss_dma=True)
+    run_parity_planned(w, 6, warm=False, dma_evict=dma, free_running=free, plan_first=True, inputs_ready=ready, miss_dma=True,
+                       staging_rows=0 if free else 2500)        # some batches miss more rows than a block holds: kernel path
+
+
+@pytest.mark.parametrize("dma", [True, False])
+def test_dma_miss_path_tiny_cache_thrashing(torch_cuda, dma):
+    """Rows evicted by one batch and missed by the next: with the DMA evict transmitter they are in transit and must come
+    from the evicted-row block, not from the host table the gather threads read."""
+    from tests.tiny_workload import TinyWorkload
+    w = TinyWorkload(num_rows=900, dim=64, cache_rows=48, seed=23, multi_hot=True, bags=24, max_bag=3, distinct_cap=40)
+    for free in (False, True):
+        run_parity_planned(w, 40, warm=True, dma_evict=dma, free_running=free, inputs_ready=True, miss_dma=True)
+    run_parity_planned(w, 24, warm=False, dma_evict=dma, free_running=True, miss_dma=True, staging_rows=16)
+
+
 @pytest.mark.parametrize("dma", [True, False])
 @pytest.mark.parametrize("free", [True, False])
 def test_planned_inputs_ready_tiny_cache_thrashing(torch_cuda, dma, free):

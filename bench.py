@@ -106,6 +106,10 @@ def main():
                          "plain (default with the other transmitters): cache_prepare(t), fwd(t), bwd(t), everything on one stream; "
                          "lookahead: cache_prepare_next(t+1) before fwd(t), bwd(t) - a different cache policy (the previous "
                          "batch's rows are protected too), not the headline configuration")
+    ap.add_argument("--miss-path", choices=("kernel", "dma"), default="kernel",
+                    help="pipelined schedule: how the planned batch's missing rows cross the link: kernel = read by a kernel from "
+                         "the mapped host table (default); dma = gathered by host threads into a pinned block and carried by "
+                         "hipMemcpyAsync (FC_MISS_DMA)")
     ap.add_argument("--dirty-tracking", action="store_true",
                     help="FC_DIRTY_TRACK: only victims updated since they were loaded are written back (a variant beyond the "
                          "paper)")
@@ -149,7 +153,8 @@ def main():
     cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
                       warm=False, staged=args.transmitter == "staged", stream=stream,
                       dma_evict=args.transmitter == "dma", dirty_tracking=args.dirty_tracking, presort=not args.forward_only,
-                      inputs_ready=not args.ids_from_host)      # every batch is resident before it is handed to the library
+                      inputs_ready=not args.ids_from_host,      # every batch is resident before it is handed to the library
+                      miss_dma=args.miss_path == "dma")
     host = cache.host_weight()
     w.host_table(out=host)
     cache.warm()
@@ -465,7 +470,8 @@ def main():
                                ("cache_prepare_next(t+1) | fwd(t), bwd(t) | cache_advance" if lookahead else "cache_prepare(t), fwd(t), bwd(t)"),
                    "policy": "look-ahead (previous batch protected), %d refused" % fallbacks[0] if lookahead else
                              ("Algorithm 1, clean victims not written back" if args.dirty_tracking else "Algorithm 1 as printed"),
-                   "transmitter": {"dma": "kernel miss fill + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),
+                   "transmitter": {"dma": ("kernel miss fill" if args.miss_path == "kernel" else "DMA miss path (host gather threads + hipMemcpyAsync)") +
+                                          " + DMA evict with %s host scatter threads" % os.environ.get("FC_SCATTER_THREADS", "8"),
                                    "direct": "kernels both ways", "staged": "block transmitter both ways"}[args.transmitter],
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},

@@ -231,8 +231,6 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY_START")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }   // still tuned
     c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
-    if (const char* e = getenv("FC_FWD_PAD_KB")) { const int v = atoi(e); if (v >= 0 && v <= 60) c->fwd_pad = v * 1024; }
-    if (const char* e = getenv("FC_BWD_PAD_KB")) { const int v = atoi(e); if (v >= 0 && v <= 40) c->bwd_pad = v * 1024; }
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);

@@ -121,8 +121,6 @@ struct fc_cache {
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
     bool fwd_sorted = true;         // one-lookup-per-bag batches: forward in slot order when the pairs are sorted ahead of time (tuning: FC_FWD_SORTED=0)
-    int fwd_pad = 0, bwd_pad = 0;   // experiment (FC_FWD_PAD_KB / FC_BWD_PAD_KB): LDS claimed per workgroup of forward / backward beyond what
-                                    // they use, which caps how many of their workgroups share a compute unit
     bool last_one_per_bag = false;  // the batch of the latest index half has that shape
     int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
     int mark_ids_per_thread = 2;    // ids per thread of the marking kernel (tuning: FC_MARK_IPT)

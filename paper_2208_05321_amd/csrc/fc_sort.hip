@@ -66,41 +66,56 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restr
     for (int it = 0; it < ITEMS; ++it)
         if (tile0 + it * RS_THREADS + (int)threadIdx.x < n) atomicAdd(&h[(key[it] >> shift) & mask], 1);
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)d * nblk + blockIdx.x] = h[d];
+    for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)blockIdx.x * radix + d] = h[d];   // tile-major: one contiguous run per tile
     if (bad && flags) atomicOr(flags, EF_BAD_SLOT);
 }
 
-// One wavefront per digit: exclusive scan of that digit's counts over the tiles; the digit total goes to dtot.
-// The counts of RS_SCAN_K * 64 tiles are requested together before the first one is waited for.
-constexpr int RS_SCAN_K = 8;
-__global__ __launch_bounds__(256) void k_sort_scan(int32_t* ghist, int nblk, int radix, int32_t* __restrict__ dtot) {
-    const int d = (blockIdx.x * 256 + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    if (d >= radix) return;
-    int32_t* row = ghist + (size_t)d * nblk;
-    int carry = 0;
-    for (int c0 = 0; c0 < nblk; c0 += 64 * RS_SCAN_K) {
-        int v[RS_SCAN_K];
+// Exclusive scan, per digit, of the per-tile counts over the tiles, in place; the digit totals go to dtot.
+// The table is tile-major (ghist[tile * radix + digit]): a tile writes its counts, and reads its offsets back, as one
+// contiguous run (digit-major, every one of those accesses touched a sector of its own: at 2048 digits x 832 tiles the
+// two kernels around this one moved ten times the table).  Here a workgroup takes SC_DIG neighbouring digits, so that
+// its reads and writes of one tile's entries are a contiguous 64 bytes, and SC_GROUPS ranges of tiles side by side:
+// sums per range first, then each range again with its starting value.
+constexpr int SC_DIG = 16, SC_GROUPS = 32, SC_PF = 8;
+__global__ __launch_bounds__(SC_DIG * SC_GROUPS) void k_sort_scan(int32_t* ghist, int nblk, int radix, int32_t* __restrict__ dtot) {
+    __shared__ int part[SC_GROUPS][SC_DIG];
+    const int dl = threadIdx.x % SC_DIG, q = threadIdx.x / SC_DIG;
+    const int d = blockIdx.x * SC_DIG + dl;
+    const bool live = d < radix;
+    const int per = (nblk + SC_GROUPS - 1) / SC_GROUPS;
+    const int t0 = q * per, t1 = min(nblk, t0 + per);
+    int sum = 0;
+    if (live) {
+        for (int t = t0; t < t1; t += SC_PF) {
+            int v[SC_PF];
 #pragma unroll
-        for (int k = 0; k < RS_SCAN_K; ++k) {
-            const int b = c0 + k * 64 + lane;
-            const int t = row[min(b, nblk - 1)];
-            v[k] = b < nblk ? t : 0;
-        }
+            for (int k = 0; k < SC_PF; ++k) v[k] = t + k < t1 ? ghist[(size_t)(t + k) * radix + d] : 0;
 #pragma unroll
-        for (int k = 0; k < RS_SCAN_K; ++k) {
-            const int b = c0 + k * 64 + lane;
-            int x = v[k];
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                int y = __shfl_up(x, o);
-                if (lane >= o) x += y;
-            }
-            if (b < nblk) row[b] = carry + x - v[k];
-            carry += __shfl(x, 63);
+            for (int k = 0; k < SC_PF; ++k) sum += v[k];
         }
     }
-    if (lane == 0) dtot[d] = carry;
+    part[q][dl] = sum;
+    __syncthreads();
+    int run = 0, tot = 0;
+#pragma unroll
+    for (int g = 0; g < SC_GROUPS; ++g) {
+        const int s = part[g][dl];
+        if (g < q) run += s;
+        tot += s;
+    }
+    if (live) {
+        for (int t = t0; t < t1; t += SC_PF) {
+            int v[SC_PF];
+#pragma unroll
+            for (int k = 0; k < SC_PF; ++k) v[k] = t + k < t1 ? ghist[(size_t)(t + k) * radix + d] : 0;
+#pragma unroll
+            for (int k = 0; k < SC_PF; ++k) {
+                if (t + k < t1) ghist[(size_t)(t + k) * radix + d] = run;
+                run += v[k];
+            }
+        }
+        if (q == 0) dtot[d] = tot;
+    }
 }
 
 template <int SRC, int ITEMS>
@@ -145,7 +160,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
         for (int k = 0; k < per; ++k) {
             const int d = d0 + k;
             if (d < radix) {
-                base[d] = run + ghist[(size_t)d * nblk + blockIdx.x];
+                base[d] = run + ghist[(size_t)blockIdx.x * radix + d];
                 run += dtot[d];
             }
         }
@@ -211,7 +226,7 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     }
     if (SRC == SORT_SRC_RANKS) {        // the slots are written now: the rest of the pass reads them
         ProfScope ps(j.prof, P_SORT_SCAN, st);
-        k_sort_scan<<<(unsigned)cdiv((int64_t)radix * 64, 256), 256, 0, st>>>(j.ghist, nblk, radix, j.dtot);
+        k_sort_scan<<<(unsigned)cdiv(radix, SC_DIG), SC_DIG * SC_GROUPS, 0, st>>>(j.ghist, nblk, radix, j.dtot);
     }
     if (SRC == SORT_SRC_RANKS) {
         ProfScope ps(j.prof, P_SORT_SCATTER, st);
@@ -221,7 +236,7 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     }
     {
         ProfScope ps(j.prof, P_SORT_SCAN, st);
-        k_sort_scan<<<(unsigned)cdiv((int64_t)radix * 64, 256), 256, 0, st>>>(j.ghist, nblk, radix, j.dtot);
+        k_sort_scan<<<(unsigned)cdiv(radix, SC_DIG), SC_DIG * SC_GROUPS, 0, st>>>(j.ghist, nblk, radix, j.dtot);
     }
     {
         ProfScope ps(j.prof, P_SORT_SCATTER, st);

@@ -141,7 +141,12 @@ enum {
  *                         measured fetch / block-copy durations); FC_FILL_BLOCKS_EARLY_START only moves the start
  *   FC_EVICT_BLOCKS, FC_EVICT_EARLY   width and start of the host-table store kernel (transmitter without FC_EVICT_DMA)
  *   FC_SCATTER_THREADS    host threads of FC_EVICT_DMA (8)
- *   FC_FWD_BAGS           bags per row-group of the forward kernel for one-lookup bags: 1, 2 or 4 (4)
+ *   FC_GATHER_THREADS     host threads of FC_MISS_DMA (6)
+ *   FC_FWD_SORTED         0: batches with one lookup per bag are always pooled in bag order (default 1: in slot order, from
+ *                         the pairs cache_prepare has sorted ahead of time for the backward pass, when those are at hand)
+ *   FC_FWD_BAGS           bags per row-group of the bag-order forward kernel for one-lookup bags: 1, 2 or 4 (4)
+ *   FC_SORT_BITS          most key bits per pass of a two-pass sort (11; read once per process)
+ *   FC_FETCH_CU_MASK      experiment: number of compute units the early fetch's stream may use (default: all)
  *   FC_MARK_IPT           ids per thread of the marking kernel (2)
  *   FC_TUNE_REPORT        if set, cache_destroy prints where the early-fetch workgroup count settled
  *   FC_TIMELINE           file that receives, whenever profiling totals are collected, one line "name start_us end_us"

@@ -466,6 +466,7 @@ static int sort_pairs(fc_cache* c, SortBufs& sb, hipStream_t st, const int32_t* 
     j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
     if (slots_out) { j.src = SORT_SRC_RANKS; j.keys_in = c->rbuf; j.rank_slot = c->rank_slot; j.slots_out = slots_out; }
     j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
+    j.one_per_bag = c->last_one_per_bag;      // sort_pairs serves the batch the last index half looked at
     j.keysA = sb.keysA; j.valsA = sb.valsA; j.keysB = sb.keysB; j.valsB = sb.valsB; j.ghist = sb.ghist; j.dtot = sb.dtot;
     j.prof = c;
     return radix_sort(j, st, kres, vres);

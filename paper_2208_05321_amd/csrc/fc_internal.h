@@ -337,11 +337,12 @@ struct SortJob {
     int src = SORT_SRC_PAIRS;
     const int32_t* keys_in = nullptr; const int32_t* vals_in = nullptr;
     const int64_t* offsets = nullptr; int num_bags = 0;
+    bool one_per_bag = false;                  // SORT_SRC_SLOTS / _RANKS: the caller knows that offsets[b] == b for every bag
     const int32_t* rank_slot = nullptr; int32_t* slots_out = nullptr;     // SORT_SRC_RANKS
     int n = 0, limit = 0, bits = 1;
     uint32_t* flags = nullptr;                 // device word for EF_BAD_SLOT, may be null
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;   // n ints each
-    int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints, (1 << RS_MAX_BITS) ints
+    int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints (per-tile and per-supertile tables), (1 << RS_MAX_BITS) ints
     fc_cache* prof = nullptr;                  // where to book per-kernel times, may be null
 };
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres);

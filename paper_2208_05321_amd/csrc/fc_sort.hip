@@ -7,6 +7,10 @@
 
 namespace fc {
 
+// Jobs of up to FUSE_MAX_TILES tiles run without a scan kernel: k_sort_hist also adds the counts of SS_TILES neighbouring
+// tiles up, and k_sort_scatter derives its offsets from those sums (digits of at most FUSE_MAX_BITS bits).
+constexpr int SS_TILES = 32, FUSE_MAX_TILES = 2048, FUSE_MAX_BITS = 9;
+
 // First-pass key of lookup i: its slot, or the sentinel C if the slot is out of range.
 __device__ __forceinline__ int first_key(const int32_t* __restrict__ slots, int i, int C, bool& bad) {
     const int k = slots[i];
@@ -35,6 +39,7 @@ __device__ __forceinline__ int load_key(const int32_t* __restrict__ keys_in, int
 template <int SRC, int ITEMS>
 __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restrict__ keys_in, int n, int limit, int shift,
                                                           int radix_bits, int nblk, int32_t* __restrict__ ghist,
+                                                          int32_t* __restrict__ stot,
                                                           uint32_t* flags, const int32_t* __restrict__ rank_slot,
                                                           int32_t* __restrict__ slots_out) {
     __shared__ int h[1 << RS_MAX_BITS];
@@ -66,7 +71,13 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restr
     for (int it = 0; it < ITEMS; ++it)
         if (tile0 + it * RS_THREADS + (int)threadIdx.x < n) atomicAdd(&h[(key[it] >> shift) & mask], 1);
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += RS_THREADS) ghist[(size_t)blockIdx.x * radix + d] = h[d];   // tile-major: one contiguous run per tile
+    for (int d = threadIdx.x; d < radix; d += RS_THREADS) {
+        const int cnt = h[d];
+        ghist[(size_t)blockIdx.x * radix + d] = cnt;   // tile-major: one contiguous run per tile
+        // counts of SS_TILES neighbouring tiles added up (the table starts at zero): the scatter kernel builds its
+        // offsets from these and from the counts of the few tiles before it, and no scan kernel runs in between
+        if (stot && cnt) atomicAdd(&stot[(size_t)(blockIdx.x / SS_TILES) * radix + d], cnt);
+    }
     if (bad && flags) atomicOr(flags, EF_BAD_SLOT);
 }
 
@@ -118,7 +129,10 @@ __global__ __launch_bounds__(SC_DIG * SC_GROUPS) void k_sort_scan(int32_t* ghist
     }
 }
 
-template <int SRC, int ITEMS>
+// FUSED: `dtot` holds the per-supertile digit counts written by k_sort_hist instead of the digit totals, and `ghist` the
+// raw per-tile counts (no scan kernel has run).  OPB (SORT_SRC_SLOTS only): bag b holds exactly lookup b, as checked by
+// the caller, so the value of lookup i is i and the offsets are not read.
+template <int SRC, int ITEMS, bool FUSED, bool OPB>
 __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __restrict__ keys_in,
                                                              const int32_t* __restrict__ vals_in,
                                                              const int64_t* __restrict__ offsets, int num_bags, int n,
@@ -143,14 +157,46 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
     for (int it = 0; it < ITEMS; ++it) {
         const int i = min(tile0 + it * 64 + lane, n - 1);
         key[it] = load_key<SRC>(keys_in, i, limit, bad);
-        if (SRC == SORT_SRC_SLOTS) {           // bag of lookup i, first guess: one lookup per bag
+        if (SRC == SORT_SRC_SLOTS && OPB) val[it] = i;
+        else if (SRC == SORT_SRC_SLOTS) {      // bag of lookup i, first guess: one lookup per bag
             const int g = min(i, num_bags - 1);
             o0[it] = offsets[g];
             o1[it] = offsets[g + 1];
         } else if (SRC == SORT_SRC_COUNTS) val[it] = i;
         else val[it] = vals_in[i];
     }
-    {   // digit bases: exclusive scan of the digit totals, plus this tile's offset within the digit
+    if (FUSED) {
+        // digit totals = sum over the supertiles; this tile's offset within a digit = the supertiles before its own plus
+        // the tiles before it inside its own.  A thread owns `per` <= 2 neighbouring digits (radix <= 512).
+        const int nsup = (nblk + SS_TILES - 1) / SS_TILES, mysup = blockIdx.x / SS_TILES;
+        const int per = (radix + RS_THREADS - 1) / RS_THREADS;
+        const int d0 = tid * per;
+        int tot[2] = {0, 0}, bef[2] = {0, 0};
+        if (d0 < radix) {
+#pragma unroll 8
+            for (int s = 0; s < nsup; ++s) {
+                const int v0 = dtot[(size_t)s * radix + d0];
+                const int v1 = per > 1 ? dtot[(size_t)s * radix + d0 + 1] : 0;
+                tot[0] += v0; tot[1] += v1;
+                if (s < mysup) { bef[0] += v0; bef[1] += v1; }
+            }
+#pragma unroll 8
+            for (int t = mysup * SS_TILES; t < (int)blockIdx.x; ++t) {
+                bef[0] += ghist[(size_t)t * radix + d0];
+                if (per > 1) bef[1] += ghist[(size_t)t * radix + d0 + 1];
+            }
+        }
+        int total;
+        int run = block_excl_scan<RS_THREADS>(tot[0] + tot[1], total, lds);
+        if (d0 < radix) {
+            base[d0] = run + bef[0];
+            if (per > 1) base[d0 + 1] = run + tot[0] + bef[1];
+        }
+        for (int d = tid; d < radix; d += RS_THREADS) {
+#pragma unroll
+            for (int k = 0; k < NW; ++k) wc[k][d] = 0;
+        }
+    } else {   // digit bases: exclusive scan of the digit totals, plus this tile's offset within the digit
         const int per = (radix + RS_THREADS - 1) / RS_THREADS;
         const int d0 = tid * per;
         int local = 0;
@@ -170,7 +216,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
         }
     }
     __syncthreads();
-    if (SRC == SORT_SRC_SLOTS) {
+    if (SRC == SORT_SRC_SLOTS && !OPB) {
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
             const int i = min(tile0 + it * 64 + lane, n - 1);
@@ -215,60 +261,109 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
 }
 
 
-template <int SRC, int ITEMS = RS_ITEMS>
+__global__ __launch_bounds__(256) void k_sort_zero(int32_t* __restrict__ p, int words) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int i = (blockIdx.x * 4 + k) * 256 + threadIdx.x;
+        if (i < words) p[i] = 0;
+    }
+}
+
+template <int SRC, bool FUSED, bool OPB, int ITEMS = RS_ITEMS>
 static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
-                        int shift, int rb) {
+                        int shift, int rb, int32_t* stot) {
     const int radix = 1 << rb;
     const int nblk = (int)cdiv(j.n, RS_THREADS * ITEMS);
     {
         ProfScope ps(j.prof, P_SORT_HIST, st);
-        k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, j.flags, j.rank_slot, j.slots_out);
+        k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, FUSED ? stot : nullptr,
+                                                                     j.flags, j.rank_slot, j.slots_out);
     }
-    if (SRC == SORT_SRC_RANKS) {        // the slots are written now: the rest of the pass reads them
+    if (!FUSED) {
         ProfScope ps(j.prof, P_SORT_SCAN, st);
         k_sort_scan<<<(unsigned)cdiv(radix, SC_DIG), SC_DIG * SC_GROUPS, 0, st>>>(j.ghist, nblk, radix, j.dtot);
     }
-    if (SRC == SORT_SRC_RANKS) {
-        ProfScope ps(j.prof, P_SORT_SCATTER, st);
-        k_sort_scatter<SORT_SRC_SLOTS, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(j.slots_out, vin, j.offsets, j.num_bags, j.n, j.limit, shift, rb,
-                                                                                     nblk, j.ghist, j.dtot, kout, vout);
-        return;
-    }
-    {
-        ProfScope ps(j.prof, P_SORT_SCAN, st);
-        k_sort_scan<<<(unsigned)cdiv(radix, SC_DIG), SC_DIG * SC_GROUPS, 0, st>>>(j.ghist, nblk, radix, j.dtot);
-    }
-    {
-        ProfScope ps(j.prof, P_SORT_SCATTER, st);
-        k_sort_scatter<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, vin, j.offsets, j.num_bags, j.n, j.limit, shift, rb,
-                                                                         nblk, j.ghist, j.dtot, kout, vout);
+    // SORT_SRC_RANKS: the slots are written now, the rest of the pass reads them
+    constexpr int SSRC = SRC == SORT_SRC_RANKS ? SORT_SRC_SLOTS : SRC;
+    ProfScope ps(j.prof, P_SORT_SCATTER, st);
+    k_sort_scatter<SSRC, ITEMS, FUSED, OPB><<<(unsigned)nblk, RS_THREADS, 0, st>>>(SRC == SORT_SRC_RANKS ? j.slots_out : kin, vin, j.offsets, j.num_bags,
+                                                                                  j.n, j.limit, shift, rb, nblk, j.ghist, FUSED ? stot : j.dtot, kout, vout);
+}
+
+template <bool FUSED, int ITEMS>
+static void first_pass(const SortJob& j, hipStream_t st, int32_t* kout, int32_t* vout, int rb, int32_t* stot) {
+    const bool opb = j.one_per_bag && j.n == j.num_bags;
+    if (j.src == SORT_SRC_PAIRS) launch_pass<SORT_SRC_PAIRS, FUSED, false, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
+    else if (j.src == SORT_SRC_COUNTS) launch_pass<SORT_SRC_COUNTS, FUSED, false, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
+    else if (j.src == SORT_SRC_SLOTS) {
+        if (opb) launch_pass<SORT_SRC_SLOTS, FUSED, true, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
+        else launch_pass<SORT_SRC_SLOTS, FUSED, false, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
+    } else {
+        if (opb) launch_pass<SORT_SRC_RANKS, FUSED, true, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
+        else launch_pass<SORT_SRC_RANKS, FUSED, false, ITEMS>(j, st, j.keys_in, j.vals_in, kout, vout, 0, rb, stot);
     }
 }
 
-int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
-    // Two passes up to 22 key bits: every pass is three launches bound by latency rather than by bytes, so a third pass
-    // costs more than the larger digit tables of 10- and 11-bit digits do; beyond that, passes of at most 8 bits.
-    // (FC_SORT_BITS, read once per process, lowers the two-pass limit per pass for experiments.)
-    static const int two_pass_bits = [] {
-        const char* e = getenv("FC_SORT_BITS");
-        const int v = e ? atoi(e) : 0;
-        return (v >= 4 && v <= RS_TWO_PASS_BITS) ? v : RS_TWO_PASS_BITS;
-    }();
-    const int passes = j.bits <= 2 * two_pass_bits ? (j.bits + two_pass_bits - 1) / two_pass_bits : (j.bits + 7) / 8;
-    const int rb = (j.bits + passes - 1) / passes;
+template <bool FUSED, int ITEMS>
+static void run_passes(const SortJob& j, hipStream_t st, int passes, int rb, int32_t* stot, size_t stot_pass,
+                       const int32_t** kres, const int32_t** vres) {
     const int32_t* kin = j.keys_in; const int32_t* vin = j.vals_in;
     int32_t* kout = j.keysA; int32_t* vout = j.valsA;
     for (int p = 0; p < passes; ++p) {
-        const int shift = p * rb;
-        if (p > 0 || j.src == SORT_SRC_PAIRS) launch_pass<SORT_SRC_PAIRS>(j, st, kin, vin, kout, vout, shift, rb);
-        else if (j.src == SORT_SRC_SLOTS) launch_pass<SORT_SRC_SLOTS>(j, st, kin, vin, kout, vout, shift, rb);
-        else if (j.src == SORT_SRC_RANKS) launch_pass<SORT_SRC_RANKS>(j, st, kin, vin, kout, vout, shift, rb);
-        else launch_pass<SORT_SRC_COUNTS>(j, st, kin, vin, kout, vout, shift, rb);
+        int32_t* sp = FUSED ? stot + stot_pass * p : nullptr;
+        if (p == 0) first_pass<FUSED, ITEMS>(j, st, kout, vout, rb, sp);
+        else launch_pass<SORT_SRC_PAIRS, FUSED, false, ITEMS>(j, st, kin, vin, kout, vout, p * rb, rb, sp);
         kin = kout; vin = vout;
         if (kout == j.keysA) { kout = j.keysB; vout = j.valsB; } else { kout = j.keysA; vout = j.valsA; }
     }
-    FC_HIP(hipGetLastError());
     *kres = kin; *vres = vin;
+}
+
+static int env_int(const char* name, int lo, int hi, int dflt) {
+    const char* e = getenv(name);
+    if (!e) return dflt;
+    const int v = atoi(e);
+    return (v >= lo && v <= hi) ? v : dflt;
+}
+
+int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
+    // Every pass is a chain of short launches bound by latency rather than by bytes.  Batches of up to FUSE_MAX_TILES
+    // tiles take passes of at most 9 bits, each two launches (counts, then offsets and scatter in one kernel; the
+    // per-supertile counts make the scan in between unnecessary); 7-bit digits leave runs of 16 keys per digit and tile,
+    // i.e. whole sectors to write, where 11-bit digits left single keys.  Larger jobs (the static module's ranking) keep
+    // the scan kernel: two passes up to 22 key bits, beyond that passes of at most 8 bits.
+    // (FC_SORT_BITS, FC_SORT_FUSED: read once per process, for experiments.)
+    static const int env_bits = env_int("FC_SORT_BITS", 4, RS_TWO_PASS_BITS, 0);
+    static const int env_fused = env_int("FC_SORT_FUSED", 0, 1, 1);
+    const int64_t nblk = cdiv(j.n, RS_TILE);
+    int passes, rb;
+    // up to 18 key bits two passes with a scan kernel each are the shorter chain (measured at 426 k pairs of 18 bits)
+    bool fused = env_fused && nblk <= FUSE_MAX_TILES && (env_bits || j.bits > 2 * FUSE_MAX_BITS);
+    if (fused) {
+        const int lim = env_bits ? (env_bits < FUSE_MAX_BITS ? env_bits : FUSE_MAX_BITS) : FUSE_MAX_BITS;
+        passes = (j.bits + lim - 1) / lim;
+        rb = (j.bits + passes - 1) / passes;
+        // the supertile tables live behind the per-tile table, inside the (tiles << RS_MAX_BITS) ints of ghist
+        const int64_t nsup = cdiv(nblk, SS_TILES);
+        if ((nblk + passes * nsup) << rb > nblk << RS_MAX_BITS) fused = false;
+    }
+    if (!fused) {
+        const int two = env_bits ? env_bits : RS_TWO_PASS_BITS;
+        passes = j.bits <= 2 * two ? (j.bits + two - 1) / two : (j.bits + 7) / 8;
+        rb = (j.bits + passes - 1) / passes;
+    }
+    int32_t* stot = nullptr;
+    size_t stot_pass = 0;
+    if (fused) {
+        stot = j.ghist + (nblk << rb);
+        stot_pass = (size_t)cdiv(nblk, SS_TILES) << rb;
+        // a fill kernel rather than a memset node: this sort may be recorded into a graph by a caller of the backward pass
+        const int64_t words = (int64_t)stot_pass * passes;
+        k_sort_zero<<<(unsigned)cdiv(words, 1024), 256, 0, st>>>(stot, (int)words);
+    }
+    if (fused) run_passes<true, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres);
+    else run_passes<false, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres);
+    FC_HIP(hipGetLastError());
     return FC_OK;
 }
 

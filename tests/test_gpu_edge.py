@@ -54,6 +54,27 @@ def test_hot_rows_long_runs(torch_cuda):
     run_parity(w, 5, warm=True)
 
 
+@pytest.mark.parametrize("multi_hot", [False, True])
+@pytest.mark.parametrize("cache_rows", [300000, 1048581])
+def test_large_cache_many_key_bits(torch_cuda, multi_hot, cache_rows):
+    """Caches of more than 2^18 slots: the backward's sort then takes three or more passes without a scan kernel (the
+    small caches of the other tests take the two-pass path with one).  One lookup per bag (values = positions, offsets
+    not read) and multi-hot bags; several tiles, a ragged tail, hot rows whose runs cross tiles."""
+    bags = 9000 if multi_hot else 23000
+    w = TinyWorkload(num_rows=2 * cache_rows + 1000, dim=4, cache_rows=cache_rows, seed=41, multi_hot=multi_hot, bags=bags,
+                     max_bag=5, hot=[3, 77, 4242], distinct_cap=6000, allow_empty=True)
+    run_parity(w, 4, warm=False)
+    run_parity(w, 3, warm=True)
+
+
+def test_large_cache_planned_schedule(torch_cuda):
+    """The same sort path as started by cache_plan_next (slot write-out folded into its first kernel)."""
+    from tests.parity import run_parity_planned
+    w = TinyWorkload(num_rows=700000, dim=8, cache_rows=300000, seed=43, multi_hot=False, bags=30000, hot=[5, 9],
+                     distinct_cap=8000)
+    run_parity_planned(w, 5, warm=True, dma_evict=True, free_running=True, inputs_ready=True)
+
+
 def test_single_id_batches(torch_cuda):
     """Degenerate: every lookup is the same row (one run over the whole batch), and a one-lookup batch."""
     torch = torch_cuda

@@ -91,7 +91,10 @@ enum {
                                stream.  The library then starts the index work of the planned batch without waiting for the
                                caller's stream at all (only the slot write-out and the sort still wait for the backward pass
                                that last read those buffers), which puts the planned batch's index decisions and row fetch a
-                               whole step ahead of cache_advance.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
+                               whole step ahead of cache_advance, and lets the sort's later passes run on the stream of the
+                               evicted-row block instead of holding up the next batch's index kernels.  Worth it where HBM
+                               binds the step (large batches, high hit ratio); where the host link binds it, the extra overlap
+                               slows the link transfers down.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
     FC_MISS_DMA = 64,       /* cache_plan_next only, with FC_EVICT_DMA or the default transmitter: the planned batch's missing rows
                                cross the link the way the paper's transmitter moves them (Section 4.3), pipelined: their list
                                is copied to the host, library-owned host threads (FC_GATHER_THREADS, default 6) gather the
@@ -142,6 +145,8 @@ enum {
  *   FC_EVICT_BLOCKS, FC_EVICT_EARLY   width and start of the host-table store kernel (transmitter without FC_EVICT_DMA)
  *   FC_SCATTER_THREADS    host threads of FC_EVICT_DMA (8)
  *   FC_GATHER_THREADS     host threads of FC_MISS_DMA (6)
+ *   FC_SORT_TAIL          0: with FC_INPUTS_READY the whole sort stays on the index stream (default 1: passes after the first
+ *                         on the side stream)
  *   FC_FWD_SORTED         0: batches with one lookup per bag are always pooled in bag order (default 1: in slot order, from
  *                         the pairs cache_prepare has sorted ahead of time for the backward pass, when those are at hand)
  *   FC_FWD_BAGS           bags per row-group of the bag-order forward kernel for one-lookup bags: 1, 2 or 4 (4)

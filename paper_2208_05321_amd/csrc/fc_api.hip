@@ -144,14 +144,14 @@ static void destroy(fc_cache* c) {
                     (void*)c->ctl, (void*)c->stage_dev, (void*)c->stage_dev2, (void*)c->part, (void*)c->pmeta, (void*)c->pbits})
         if (p) (void)hipFree(p);
     for (SortBufs& sb : c->sb)
-        for (void* p : {(void*)sb.keysA, (void*)sb.valsA, (void*)sb.keysB, (void*)sb.valsB, (void*)sb.ghist, (void*)sb.dtot})
+        for (void* p : {(void*)sb.keysA, (void*)sb.valsA, (void*)sb.keysB, (void*)sb.valsB, (void*)sb.ghist, (void*)sb.dtot, (void*)sb.stot[0], (void*)sb.stot[1]})
             if (p) (void)hipFree(p);
     for (PresortRec& r : c->rec) if (r.ev_sorted) (void)hipEventDestroy(r.ev_sorted);
     for (void* p : {(void*)c->hctl, (void*)c->stage_pin, (void*)c->list_pin}) if (p) (void)hipHostFree(p);
     if (c->own_host && c->host) (void)hipHostFree(c->host);
     for (const ProfSpan& sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_assign_done, c->ev_emit_done, c->ev_quiesce, c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_sort_tail, c->ev_assign_done, c->ev_emit_done, c->ev_quiesce, c->ev_evict_done, c->ev_gather_done, c->ev_slots, c->ev_s_now, c->ev_pre_done, c->ev_index_done, c->ev_move_done[0], c->ev_move_done[1]}) if (e) (void)hipEventDestroy(e);
     if (c->side) (void)hipStreamDestroy(c->side);
     if (c->pre) (void)hipStreamDestroy(c->pre);
     if (c->pf) (void)hipStreamDestroy(c->pf);
@@ -231,6 +231,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     if (const char* e = getenv("FC_FILL_BLOCKS_EARLY_START")) { const int v = atoi(e); if (v >= 1) c->fill_blocks_early = v; }   // still tuned
     c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
+    if (const char* e = getenv("FC_SORT_TAIL")) c->sort_tail_side = atoi(e) != 0;
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
@@ -320,7 +321,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     c->aux = c->pf;
     c->pst = c->last_pst = c->stream;
     c->presort = (flags & FC_NO_PRESORT) == 0;
-    for (hipEvent_t* e : {&c->ev_assign_done, &c->ev_emit_done, &c->ev_quiesce, &c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
+    for (hipEvent_t* e : {&c->ev_sort_tail, &c->ev_assign_done, &c->ev_emit_done, &c->ev_quiesce, &c->ev_evict_done, &c->ev_gather_done, &c->ev_slots, &c->ev_s_now, &c->ev_pre_done, &c->ev_index_done, &c->ev_move_done[0], &c->ev_move_done[1], &c->ev_arrive[0], &c->ev_arrive[1],
                           &c->rec[0].ev_sorted, &c->rec[1].ev_sorted})
         FC_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
     if (c->dma_evict) {

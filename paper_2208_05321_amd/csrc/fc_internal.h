@@ -66,7 +66,14 @@ struct GatherPool;    // host threads that gather missing rows into a pinned blo
 struct SortBufs {
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr, *ghist = nullptr, *dtot = nullptr;
     int64_t cap = 0, ghist_cap = 0;
+    // Per-supertile digit counts of the scan-free passes (SORT_STOT_WORDS ints each).  They are accumulated with atomics
+    // and so have to start at zero: a sort uses set `zset`, which is clean, and its first kernel clears what the sort
+    // before it left in the other set (`dirty` words from the start), so no launch is spent on clearing.
+    int32_t* stot[2] = {nullptr, nullptr};
+    int zset = 0;
+    int64_t dirty[2] = {0, 0};
 };
+constexpr int64_t SORT_STOT_WORDS = 131072;
 // What the row-movement half of a cache_prepare has to do (decided by the index half).
 // evicted-row blocks of the DMA evict transmitter that may be on their way at once
 #ifndef FC_DMA_BLOCKS
@@ -82,6 +89,8 @@ struct PresortRec {
     int64_t n = 0, bags = 0;
     const int32_t *keys = nullptr, *vals = nullptr;
     hipEvent_t ev_sorted = nullptr;
+    hipStream_t sort_stream = nullptr;  // where ev_sorted was last recorded (null: never)
+    bool caller_waited = false;         // the caller's stream already waits for ev_sorted (forward before backward)
 };
 
 }  // namespace fc
@@ -120,6 +129,8 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    bool sort_tail_side = true;     // cache_plan_next: the sort's passes after the first run on the side stream (tuning: FC_SORT_TAIL=0)
+    hipEvent_t ev_sort_tail = nullptr;
     bool fwd_sorted = true;         // one-lookup-per-bag batches: forward in slot order when the pairs are sorted ahead of time (tuning: FC_FWD_SORTED=0)
     bool last_one_per_bag = false;  // the batch of the latest index half has that shape
     int fwd_bags = 4;               // bags per row-group of the forward kernel for one-lookup-per-bag batches: 1, 2 or 4 (tuning: FC_FWD_BAGS)
@@ -342,7 +353,15 @@ struct SortJob {
     int n = 0, limit = 0, bits = 1;
     uint32_t* flags = nullptr;                 // device word for EF_BAD_SLOT, may be null
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;   // n ints each
-    int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints (per-tile and per-supertile tables), (1 << RS_MAX_BITS) ints
+    int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints, (1 << RS_MAX_BITS) ints
+    // scan-free passes (optional): a clean table of stot_cap ints to accumulate into; the first kernel also clears the first
+    // other_dirty ints of stot_other; *dirtied receives how many ints of stot this sort has written to
+    int32_t *stot = nullptr, *stot_other = nullptr;
+    int64_t stot_cap = 0, other_dirty = 0;
+    int64_t* dirtied = nullptr;
+    // optional: the passes after the first run on tail_stream (ordered behind the first by tail_event), so that the stream
+    // of the first pass is free again sooner; *last_stream receives the stream the last pass ran on
+    hipStream_t tail_stream = nullptr; hipEvent_t tail_event = nullptr; hipStream_t* last_stream = nullptr;
     fc_cache* prof = nullptr;                  // where to book per-kernel times, may be null
 };
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres);

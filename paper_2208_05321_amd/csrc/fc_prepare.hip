@@ -127,12 +127,21 @@ __global__ __launch_bounds__(MARK_THREADS) void k_remap_mark(const int64_t* __re
 
 // ---------------------------------------------------------------------------------------------------------
 // K2a  per rank-space tile: rows used, rows missing, rows evictable.
+//      On the way (DMA evict transmitter): the block that this batch's victims will go to has reached the host table, so
+//      rows still marked as in transit in it become plain "not resident" (what k_clear_transit does; folded in here
+//      because nothing before K3 reads rank_slot, and a launch of its own lengthened the index chain).
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(RT_THREADS) void k_rank_count(const uint4* __restrict__ ubits4,
                                                            const uint4* __restrict__ rbits4,
                                                            const uint4* __restrict__ pbits4, int protect_prev,
-                                                           int32_t* __restrict__ bsum, int NB) {
+                                                           int32_t* __restrict__ bsum, int NB,
+                                                           const int32_t* __restrict__ landed_ranks, int landed, int landed_base,
+                                                           int32_t* rank_slot) {
     __shared__ int lds[3][RT_THREADS / 64];
+    for (int j = blockIdx.x * RT_THREADS + threadIdx.x; j < landed; j += gridDim.x * RT_THREADS) {
+        const int r = landed_ranks[j];
+        if (rank_slot[r] == -2 - (landed_base + j)) rank_slot[r] = -1;
+    }
     const size_t idx = (size_t)blockIdx.x * RT_THREADS + threadIdx.x;
     const uint4 u = ubits4[idx];
     uint4 r = rbits4[idx];
@@ -667,16 +676,14 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     const int32_t ticket = c->ticket = (c->ticket + 1) & 0x7fffffff;
     const int protect_prev = lookahead ? 1 : 0;
     int transit_base = -1, buf = 0;
+    int64_t landed = 0;
     if (c->dma_evict) {
         // the block this call may fill was handed over DMA_BLOCKS blocks ago: its rows must be in the host table by now
         const uint64_t seq = pool_published(c) + 1;
         buf = (int)(seq % DMA_BLOCKS);
         if (seq > DMA_BLOCKS) pool_wait(c, seq - DMA_BLOCKS);
-        if (c->blk_rows[buf] > 0) {
-            k_clear_transit<<<(unsigned)cdiv(c->blk_rows[buf], 256), 256, 0, st>>>(c->vrank_buf[buf], (int)c->blk_rows[buf],
-                                                                                (int)(buf * c->staging_rows), c->rank_slot);
-            c->blk_rows[buf] = 0;
-        }
+        landed = c->blk_rows[buf];            // cleared by k_rank_count below, before anything reads rank_slot or rewrites the list
+        c->blk_rows[buf] = 0;
         if (!c->dirty_track) c->vrank = c->vrank_buf[buf];
         transit_base = (int)(buf * c->staging_rows);
     }
@@ -695,7 +702,9 @@ int prepare_index(fc_cache* c, hipStream_t st, bool lookahead, const int64_t* id
     {
         ProfScope ps(c, P_RANK_COUNT, st);
         k_rank_count<<<(unsigned)c->NB, RT_THREADS, 0, st>>>((const uint4*)c->ubits, (const uint4*)c->rbits, (const uint4*)c->pbits,
-                                                            protect_prev, c->bsum, (int)c->NB);
+                                                            protect_prev, c->bsum, (int)c->NB,
+                                                            c->dma_evict ? c->vrank_buf[buf] : nullptr, (int)landed,
+                                                            (int)(buf * c->staging_rows), c->rank_slot);
     }
     {
         ProfScope ps(c, P_RANK_PLAN, st);

@@ -41,8 +41,14 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_hist(const int32_t* __restr
                                                           int radix_bits, int nblk, int32_t* __restrict__ ghist,
                                                           int32_t* __restrict__ stot,
                                                           uint32_t* flags, const int32_t* __restrict__ rank_slot,
-                                                          int32_t* __restrict__ slots_out) {
+                                                          int32_t* __restrict__ slots_out,
+                                                          int32_t* __restrict__ zero_ptr, int zero_words) {
     __shared__ int h[1 << RS_MAX_BITS];
+    if (zero_ptr) {     // what the previous sort left in the other set of supertile tables, a slice per workgroup
+        const int per = (zero_words + (int)gridDim.x - 1) / (int)gridDim.x;
+        const int z1 = min(zero_words, ((int)blockIdx.x + 1) * per);
+        for (int i = (int)blockIdx.x * per + (int)threadIdx.x; i < z1; i += RS_THREADS) zero_ptr[i] = 0;
+    }
     const int radix = 1 << radix_bits, mask = radix - 1;
     const int tile0 = blockIdx.x * (RS_THREADS * ITEMS);
     // all of the tile's keys are requested before anything waits for one (a lane beyond n rereads the last key)
@@ -261,14 +267,6 @@ __global__ __launch_bounds__(RS_THREADS) void k_sort_scatter(const int32_t* __re
 }
 
 
-__global__ __launch_bounds__(256) void k_sort_zero(int32_t* __restrict__ p, int words) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int i = (blockIdx.x * 4 + k) * 256 + threadIdx.x;
-        if (i < words) p[i] = 0;
-    }
-}
-
 template <int SRC, bool FUSED, bool OPB, int ITEMS = RS_ITEMS>
 static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, const int32_t* vin, int32_t* kout, int32_t* vout,
                         int shift, int rb, int32_t* stot) {
@@ -276,8 +274,10 @@ static void launch_pass(const SortJob& j, hipStream_t st, const int32_t* kin, co
     const int nblk = (int)cdiv(j.n, RS_THREADS * ITEMS);
     {
         ProfScope ps(j.prof, P_SORT_HIST, st);
+        const bool first = shift == 0 && j.stot_other && j.other_dirty > 0;
         k_sort_hist<SRC, ITEMS><<<(unsigned)nblk, RS_THREADS, 0, st>>>(kin, j.n, j.limit, shift, rb, nblk, j.ghist, FUSED ? stot : nullptr,
-                                                                     j.flags, j.rank_slot, j.slots_out);
+                                                                     j.flags, j.rank_slot, j.slots_out,
+                                                                     first ? j.stot_other : nullptr, first ? (int)j.other_dirty : 0);
     }
     if (!FUSED) {
         ProfScope ps(j.prof, P_SORT_SCAN, st);
@@ -305,18 +305,25 @@ static void first_pass(const SortJob& j, hipStream_t st, int32_t* kout, int32_t*
 }
 
 template <bool FUSED, int ITEMS>
-static void run_passes(const SortJob& j, hipStream_t st, int passes, int rb, int32_t* stot, size_t stot_pass,
-                       const int32_t** kres, const int32_t** vres) {
+static int run_passes(const SortJob& j, hipStream_t st, int passes, int rb, int32_t* stot, size_t stot_pass,
+                      const int32_t** kres, const int32_t** vres) {
     const int32_t* kin = j.keys_in; const int32_t* vin = j.vals_in;
     int32_t* kout = j.keysA; int32_t* vout = j.valsA;
     for (int p = 0; p < passes; ++p) {
         int32_t* sp = FUSED ? stot + stot_pass * p : nullptr;
+        if (p == 1 && j.tail_stream && j.tail_event && j.tail_stream != st) {
+            FC_HIP(hipEventRecord(j.tail_event, st));
+            FC_HIP(hipStreamWaitEvent(j.tail_stream, j.tail_event, 0));
+            st = j.tail_stream;
+        }
         if (p == 0) first_pass<FUSED, ITEMS>(j, st, kout, vout, rb, sp);
         else launch_pass<SORT_SRC_PAIRS, FUSED, false, ITEMS>(j, st, kin, vin, kout, vout, p * rb, rb, sp);
         kin = kout; vin = vout;
         if (kout == j.keysA) { kout = j.keysB; vout = j.valsB; } else { kout = j.keysA; vout = j.valsA; }
     }
     *kres = kin; *vres = vin;
+    if (j.last_stream) *j.last_stream = st;
+    return FC_OK;
 }
 
 static int env_int(const char* name, int lo, int hi, int dflt) {
@@ -328,8 +335,8 @@ static int env_int(const char* name, int lo, int hi, int dflt) {
 
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
     // Every pass is a chain of short launches bound by latency rather than by bytes.  Batches of up to FUSE_MAX_TILES
-    // tiles take passes of at most 9 bits, each two launches (counts, then offsets and scatter in one kernel; the
-    // per-supertile counts make the scan in between unnecessary); 7-bit digits leave runs of 16 keys per digit and tile,
+    // tiles and more than 18 key bits take passes of at most 9 bits, each two launches (counts, then offsets and scatter in
+    // one kernel; the per-supertile counts make the scan in between unnecessary; the caller supplies their table); 7-bit digits leave runs of 16 keys per digit and tile,
     // i.e. whole sectors to write, where 11-bit digits left single keys.  Larger jobs (the static module's ranking) keep
     // the scan kernel: two passes up to 22 key bits, beyond that passes of at most 8 bits.
     // (FC_SORT_BITS, FC_SORT_FUSED: read once per process, for experiments.)
@@ -338,31 +345,24 @@ int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int
     const int64_t nblk = cdiv(j.n, RS_TILE);
     int passes, rb;
     // up to 18 key bits two passes with a scan kernel each are the shorter chain (measured at 426 k pairs of 18 bits)
-    bool fused = env_fused && nblk <= FUSE_MAX_TILES && (env_bits || j.bits > 2 * FUSE_MAX_BITS);
+    bool fused = env_fused && j.stot && nblk <= FUSE_MAX_TILES && (env_bits || j.bits > 2 * FUSE_MAX_BITS);
+    size_t stot_pass = 0;
     if (fused) {
         const int lim = env_bits ? (env_bits < FUSE_MAX_BITS ? env_bits : FUSE_MAX_BITS) : FUSE_MAX_BITS;
         passes = (j.bits + lim - 1) / lim;
         rb = (j.bits + passes - 1) / passes;
-        // the supertile tables live behind the per-tile table, inside the (tiles << RS_MAX_BITS) ints of ghist
-        const int64_t nsup = cdiv(nblk, SS_TILES);
-        if ((nblk + passes * nsup) << rb > nblk << RS_MAX_BITS) fused = false;
+        stot_pass = (size_t)cdiv(nblk, SS_TILES) << rb;
+        if ((int64_t)(stot_pass * passes) > j.stot_cap) fused = false;
     }
     if (!fused) {
         const int two = env_bits ? env_bits : RS_TWO_PASS_BITS;
         passes = j.bits <= 2 * two ? (j.bits + two - 1) / two : (j.bits + 7) / 8;
         rb = (j.bits + passes - 1) / passes;
     }
-    int32_t* stot = nullptr;
-    size_t stot_pass = 0;
-    if (fused) {
-        stot = j.ghist + (nblk << rb);
-        stot_pass = (size_t)cdiv(nblk, SS_TILES) << rb;
-        // a fill kernel rather than a memset node: this sort may be recorded into a graph by a caller of the backward pass
-        const int64_t words = (int64_t)stot_pass * passes;
-        k_sort_zero<<<(unsigned)cdiv(words, 1024), 256, 0, st>>>(stot, (int)words);
-    }
-    if (fused) run_passes<true, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres);
-    else run_passes<false, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres);
+    int32_t* stot = fused ? j.stot : nullptr;
+    if (j.dirtied) *j.dirtied = fused ? (int64_t)(stot_pass * passes) : 0;
+    if (fused) FC_TRY((run_passes<true, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres)));
+    else FC_TRY((run_passes<false, RS_ITEMS>(j, st, passes, rb, stot, stot_pass, kres, vres)));
     FC_HIP(hipGetLastError());
     return FC_OK;
 }

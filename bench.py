@@ -10,6 +10,7 @@ table in profile_pass below.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -271,16 +272,27 @@ def main():
     pipelined, lookahead = args.schedule == "pipelined", args.schedule == "lookahead"
     step = step_lookahead if lookahead else (step_planned if pipelined else step_plain)
 
+    # no collector pause inside the timed region (the loop allocates a few small Python objects per step)
+    gc.collect()
+    gc.disable()
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
     cache.check()                        # nothing of the warm-up is still on its way (host scatter threads included)
-    t_start = time.perf_counter()
+    marks = [0.0] * (args.steps + 1)
+    t_start = marks[0] = time.perf_counter()
     for t in range(args.warmup, total_steps):
         step(t)
+        marks[t - args.warmup + 1] = time.perf_counter()
     torch.cuda.synchronize()
+    t_sync = time.perf_counter()
     cache.check()                        # the clock stops once every evicted row of the timed steps is in the host table
     elapsed = time.perf_counter() - t_start
+    gc.enable()
+    # where the host spent the timed region (diagnostic: a stall of the host loop shows up as one long interval)
+    host_steps = [(b - a) * 1e3 for a, b in zip(marks, marks[1:])]
+    host_loop = {"max_ms": round(max(host_steps), 3), "median_ms": round(sorted(host_steps)[len(host_steps) // 2], 3),
+                 "drain_ms": round((t_sync - marks[-1]) * 1e3, 3), "check_ms": round((t_start + elapsed - t_sync) * 1e3, 3)}
     # one entry per prepared batch; the pipelined schedules have prepared one batch beyond the last timed step
     timed = stats[args.warmup:total_steps]
     assert len(timed) == args.steps
@@ -305,6 +317,8 @@ def main():
     mean = {k: float(np.mean([s[k] for s in timed])) for k in ("n_ids", "n_unique", "n_miss", "n_evict")}
     log(f"[bench] {args.steps} steps in {elapsed:.4f}s: {value / 1e6:.1f} M ids/s, {ms_per_step:.3f} ms/step, "
         f"hit ratio {hit_ratio:.4f}, per batch unique {mean['n_unique']:.0f} miss {mean['n_miss']:.0f}")
+    log(f"[bench] host loop per step: median {host_loop['median_ms']} ms, max {host_loop['max_ms']} ms; drain {host_loop['drain_ms']} ms, "
+        f"check {host_loop['check_ms']} ms")
 
     # ---- per-kernel pass: HIP events on the library's own streams ----
     kernels = {}
@@ -484,7 +498,7 @@ def main():
                    "ids_per_step": int(mean["n_ids"]), "unique_per_step": round(mean["n_unique"], 1),
                    "miss_per_step": round(mean["n_miss"], 1), "evict_per_step": round(mean["n_evict"], 1)},
         "ids_from_host": bool(args.ids_from_host),
-        "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5), "hit_ratio_by_phase": phases,
+        "hit_ratio": round(hit_ratio, 5), "unique_hit_ratio": round(uniq_hit_ratio, 5), "hit_ratio_by_phase": phases, "host_loop": host_loop,
         "warm_in": {"batches": args.warmup, "hit_ratio": round(warm_in_hit, 5), "timed": False},
         "roofline": roofline, "host_link": host_link, "kernels": kernels, "cpu_baseline": cpu_baseline,
     }

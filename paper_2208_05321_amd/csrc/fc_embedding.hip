@@ -442,18 +442,23 @@ static int ensure_sort(SortBufs& sb, int64_t n) {
 static int sort_in(SortJob& j, SortBufs& sb, hipStream_t st, const int32_t** kres, const int32_t** vres) {
     j.keysA = sb.keysA; j.valsA = sb.valsA; j.keysB = sb.keysB; j.valsB = sb.valsB; j.ghist = sb.ghist; j.dtot = sb.dtot;
     int64_t dirtied = 0;
+    if (sb.stot[0] && sb.stot[1] && sb.dirty[sb.zset] > 0) {     // only after a failed sort: the table to use is not known to be clean
+        FC_HIP(hipMemsetAsync(sb.stot[sb.zset], 0, (size_t)SORT_STOT_WORDS * 4, st));
+        sb.dirty[sb.zset] = 0;
+    }
     if (sb.stot[0] && sb.stot[1]) {
         j.stot = sb.stot[sb.zset]; j.stot_cap = SORT_STOT_WORDS;
         j.stot_other = sb.stot[sb.zset ^ 1]; j.other_dirty = sb.dirty[sb.zset ^ 1];
         j.dirtied = &dirtied;
     }
-    FC_TRY(radix_sort(j, st, kres, vres));
+    const int rc = radix_sort(j, st, kres, vres);
     if (j.stot) {
-        sb.dirty[sb.zset] = dirtied;
-        sb.dirty[sb.zset ^ 1] = 0;
+        // after a failed launch nothing is known about either table: both count as written to in full
+        sb.dirty[sb.zset] = rc == FC_OK ? dirtied : SORT_STOT_WORDS;
+        sb.dirty[sb.zset ^ 1] = rc == FC_OK ? 0 : SORT_STOT_WORDS;
         sb.zset ^= 1;
     }
-    return FC_OK;
+    return rc;
 }
 
 static int ensure_part(fc_cache* c, int64_t groups);

@@ -67,6 +67,32 @@ def test_large_cache_many_key_bits(torch_cuda, multi_hot, cache_rows):
     run_parity(w, 3, warm=True)
 
 
+def test_large_cache_batches_of_very_different_sizes(torch_cuda):
+    """Consecutive sorts of very different sizes on one handle (the tables of per-supertile counts alternate, and each
+    sort clears what the one before it left behind): 70k lookups, then 5, then 23k, ..., trained and compared every time."""
+    torch = torch_cuda
+    w = TinyWorkload(num_rows=700000, dim=4, cache_rows=300000, seed=47, multi_hot=False)
+    gpu, orc = make_pair(w, warm=True)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(5)
+    for t, n in enumerate([70000, 5, 23000, 2049, 70000, 1, 4096, 33000]):
+        pool = rng.permutation(w.num_rows)[: min(n, 5000)]
+        ids = pool[rng.integers(0, len(pool), size=n)].astype(np.int64)
+        ids[: n // 10] = pool[0]                                  # one hot row: a run over several tiles
+        off = np.arange(n + 1, dtype=np.int64)
+        g = rng.standard_normal((n, w.dim)).astype(np.float32)
+        so = orc.prepare(ids, off)
+        sd = gpu.prepare(torch.from_numpy(ids).to(dev), torch.from_numpy(off).to(dev))
+        compare_prepare(gpu, orc, sd.cpu().numpy(), so, t)
+        od = gpu.embedding_bag_fwd(sd, torch.from_numpy(off).to(dev))
+        assert_close(od.cpu().numpy(), orc.embedding_bag_fwd(so, off), f"batch {t}: pooled output")
+        gpu.embedding_bag_bwd_sgd(sd, torch.from_numpy(off).to(dev), torch.from_numpy(g).to(dev), 0.05)
+        orc.embedding_bag_bwd_sgd(so, off, g, 0.05)
+        assert_close(gpu.rows(), orc.cache, f"batch {t} (n={n}): cached rows")
+    gpu.check()
+    gpu.close()
+
+
 def test_large_cache_planned_schedule(torch_cuda):
     """The same sort path as started by cache_plan_next (slot write-out folded into its first kernel)."""
     from tests.parity import run_parity_planned

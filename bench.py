@@ -113,9 +113,9 @@ def main():
                          "hipMemcpyAsync (FC_MISS_DMA)")
     ap.add_argument("--inputs-ready", choices=("auto", "on", "off"), default="auto",
                     help="FC_INPUTS_READY (the batches are resident before they are handed over, so the planned batch's index "
-                         "work need not wait for the caller's stream): 3-4%% faster at config 4, whose step is bound by HBM, "
-                         "8-10%% slower where the host link binds (configs 2, 3: the early fetch then overlaps the evicted-block "
-                         "copy all the time and both slow down); auto = on for config 4 only")
+                         "work need not wait for the caller's stream): 10%% faster at config 4 while HBM binds its step; the library "
+                         "itself stops running ahead while the host link binds (configs 2, 3, config 4 after its hot set has rotated), "
+                         "where it would cost 7-10%%; auto = on unless the ids come from host memory inside the timed region")
     ap.add_argument("--dirty-tracking", action="store_true",
                     help="FC_DIRTY_TRACK: only victims updated since they were loaded are written back (a variant beyond the "
                          "paper)")
@@ -156,7 +156,7 @@ def main():
     if args.static_module:
         return bench_static_module(args, w, torch, dev)
 
-    inputs_ready = (args.inputs_ready == "on" or (args.inputs_ready == "auto" and w.name == "c4")) and not args.ids_from_host
+    inputs_ready = args.inputs_ready != "off" and not args.ids_from_host
     cache = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=args.staging_rows,
                       warm=False, staged=args.transmitter == "staged", stream=stream,
                       dma_evict=args.transmitter == "dma", dirty_tracking=args.dirty_tracking, presort=not args.forward_only,
@@ -309,7 +309,9 @@ def main():
         phases = []
         for ph in sorted({t // w.drift_every for t in range(args.warmup, total_steps)}):
             sel = [stats[t] for t in range(args.warmup, total_steps) if t // w.drift_every == ph]
-            phases.append({"batches": [ph * w.drift_every if ph * w.drift_every > args.warmup else args.warmup,
+            hs = [host_steps[t - args.warmup] for t in range(args.warmup, total_steps) if t // w.drift_every == ph]
+            phases.append({"host_ms_per_step": round(float(np.mean(hs)), 4),     # the host loop is paced by the GPU (it waits for every planning kernel)
+                           "batches": [ph * w.drift_every if ph * w.drift_every > args.warmup else args.warmup,
                                        min((ph + 1) * w.drift_every, total_steps) - 1],
                            "rotations_so_far": ph,
                            "hit_ratio": round(sum(x["n_hit_ids"] for x in sel) / max(1, sum(x["n_ids"] for x in sel)), 5),
@@ -317,6 +319,9 @@ def main():
     mean = {k: float(np.mean([s[k] for s in timed])) for k in ("n_ids", "n_unique", "n_miss", "n_evict")}
     log(f"[bench] {args.steps} steps in {elapsed:.4f}s: {value / 1e6:.1f} M ids/s, {ms_per_step:.3f} ms/step, "
         f"hit ratio {hit_ratio:.4f}, per batch unique {mean['n_unique']:.0f} miss {mean['n_miss']:.0f}")
+    if phases and len(phases) > 1:
+        log("[bench] by phase: " + "; ".join(f"batches {p['batches'][0]}-{p['batches'][1]}: {p['host_ms_per_step']:.3f} ms/step, hit ratio {p['hit_ratio']:.4f}, "
+                                             f"{p['miss_per_step']:.0f} misses" for p in phases))
     log(f"[bench] host loop per step: median {host_loop['median_ms']} ms, max {host_loop['max_ms']} ms; drain {host_loop['drain_ms']} ms, "
         f"check {host_loop['check_ms']} ms")
 

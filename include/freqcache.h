@@ -92,9 +92,11 @@ enum {
                                caller's stream at all (only the slot write-out and the sort still wait for the backward pass
                                that last read those buffers), which puts the planned batch's index decisions and row fetch a
                                whole step ahead of cache_advance, and lets the sort's later passes run on the stream of the
-                               evicted-row block instead of holding up the next batch's index kernels.  Worth it where HBM
+                               evicted-row block instead of holding up the next batch's index kernels.  That pays where HBM
                                binds the step (large batches, high hit ratio); where the host link binds it, the extra overlap
-                               slows the link transfers down.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
+                               slows the link transfers down, so the library runs ahead only while the previous batch missed
+                               at most FC_AHEAD_MISS_PCT (default 2) rows per 100 of (lookups + bags) / 2, the point where
+                               the link's bytes take as long as HBM's.  Results are unchanged.  Ignored with FC_DIRTY_TRACK. */
     FC_MISS_DMA = 64,       /* cache_plan_next only, with FC_EVICT_DMA or the default transmitter: the planned batch's missing rows
                                cross the link the way the paper's transmitter moves them (Section 4.3), pipelined: their list
                                is copied to the host, library-owned host threads (FC_GATHER_THREADS, default 6) gather the
@@ -145,6 +147,7 @@ enum {
  *   FC_EVICT_BLOCKS, FC_EVICT_EARLY   width and start of the host-table store kernel (transmitter without FC_EVICT_DMA)
  *   FC_SCATTER_THREADS    host threads of FC_EVICT_DMA (8)
  *   FC_GATHER_THREADS     host threads of FC_MISS_DMA (6)
+ *   FC_AHEAD_MISS_PCT     threshold of FC_INPUTS_READY (see there); 0 = never run ahead, 100 = always
  *   FC_SORT_TAIL          0: with FC_INPUTS_READY the whole sort stays on the index stream (default 1: passes after the first
  *                         on the side stream)
  *   FC_FWD_SORTED         0: batches with one lookup per bag are always pooled in bag order (default 1: in slot order, from

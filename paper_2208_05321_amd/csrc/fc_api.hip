@@ -232,6 +232,7 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
     if (const char* e = getenv("FC_SORT_TAIL")) c->sort_tail_side = atoi(e) != 0;
+    if (const char* e = getenv("FC_AHEAD_MISS_PCT")) { const float v = (float)atof(e); if (v >= 0.f) c->ahead_miss_pct = v; }
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }
     if (const char* e = getenv("FC_EVICT_EARLY")) c->evict_early = atoi(e);
@@ -533,7 +534,14 @@ int cache_plan_next(fc_cache* c, const int64_t* ids_dev, int64_t n, const int64_
     // library's own index state, which only index halves change); the slot write-out, the first kernel to touch a buffer
     // of the caller's, still waits.  With FC_DIRTY_TRACK the row movement of the current batch marks rows as in transit,
     // which the planned batch's decisions read: no head start then.
-    const bool early = (c->flags & FC_INPUTS_READY) && !c->dirty_track;
+    // Running ahead pays where HBM binds the step and costs where the host link does (the early fetch and the evicted-block
+    // copy then overlap all the time and slow each other down).  Which of the two it is follows from the bytes: a missing row
+    // crosses the link once each way, a lookup and a bag move one row each through HBM, and the two rates differ by a factor
+    // of about 100, so the link binds once the previous batch missed more than about 2 rows per 100 lookups-and-bags/2
+    // (config 4: 1.7 before its hot set rotates, 2.9 and 3.5 after; config 2: 9.6).  FC_AHEAD_MISS_PCT moves the threshold.
+    const bool may_run_ahead = (c->flags & FC_INPUTS_READY) && !c->dirty_track;
+    const bool early = may_run_ahead && (double)c->last.n_miss * 100.0 <= (double)c->ahead_miss_pct * 0.5 * (double)(n + num_bags);
+    c->ahead_now = early;
     if (!early) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_s_now, 0));
     // FC_DIRTY_TRACK: which victims of the current batch are in transit is only marked by its row movement
     if (c->dirty_track && c->move_stream[c->lset]) FC_HIP(hipStreamWaitEvent(c->pre, c->ev_move_done[c->lset], 0));

@@ -530,13 +530,13 @@ int presort_impl(fc_cache* c, const int32_t* slots, int64_t n, const int64_t* of
     // the record's buffers were last written by a sort that may have run on another library stream (the schedule changed)
     // (a record the caller's stream has consumed is covered by the wait for that stream above)
     if (r.sort_stream && r.sort_stream != c->aux && !r.caller_waited) FC_HIP(hipStreamWaitEvent(c->aux, r.ev_sorted, 0));
-    // cache_plan_next with FC_INPUTS_READY (the planned batch's work may run as far ahead as the library's own state allows):
+    // cache_plan_next running ahead (FC_INPUTS_READY while HBM rather than the host link binds the step):
     // the index stream is then the busiest of the schedule, and the next batch's index kernels queue behind this sort; its
     // passes after the first move to the side stream, which only carries the evicted-row block.  Where the host link binds
     // the step, that block copy fills the side stream and the sort must not delay it: measured 7% slower there, 8% faster
     // where HBM binds.
     hipStream_t last = c->aux;
-    const bool split = slots_out && c->sort_tail_side && (c->flags & FC_INPUTS_READY) && !c->dirty_track && c->aux == c->pre &&
+    const bool split = slots_out && c->sort_tail_side && c->ahead_now && c->aux == c->pre &&
                        c->side && c->side != c->aux;
     FC_TRY(sort_pairs(c, c->sb[k], c->aux, slots, n, offsets, num_bags, &r.keys, &r.vals, slots_out, split ? c->side : nullptr, &last));
     FC_HIP(hipEventRecord(r.ev_sorted, last));

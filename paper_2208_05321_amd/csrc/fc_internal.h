@@ -129,6 +129,8 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    float ahead_miss_pct = 2.0f;    // FC_INPUTS_READY: run ahead while the previous batch's misses stay below this share (tuning: FC_AHEAD_MISS_PCT)
+    bool ahead_now = false;         // the cache_plan_next in progress runs ahead of the caller's stream
     bool sort_tail_side = true;     // cache_plan_next: the sort's passes after the first run on the side stream (tuning: FC_SORT_TAIL=0)
     hipEvent_t ev_sort_tail = nullptr;
     bool fwd_sorted = true;         // one-lookup-per-bag batches: forward in slot order when the pairs are sorted ahead of time (tuning: FC_FWD_SORTED=0)

@@ -1,6 +1,8 @@
-// Stable LSD radix sort of (key, value) int32 pairs, 64-wide wavefronts, up to 9 bits per pass.
-// Used by the backward pass (sort lookups by slot, value = bag) and by the static-module build
-// (sort ids by descending count).  Keys come from one of three sources, see SortSrc.
+// Stable LSD radix sort of (key, value) int32 pairs, 64-wide wavefronts, tiles of RS_TILE keys per workgroup.
+// Used by the backward pass and the slot-order forward (sort lookups by slot, value = bag) and by the static-module
+// build (sort ids by descending count).  Keys come from one of four sources, see SortSrc.  A pass is either
+// count -> scan -> scatter (up to RS_MAX_BITS bits per digit) or, for batch-sized jobs with many key bits, count -> scatter
+// with per-supertile sums in place of the scan (see radix_sort for which is chosen when).
 #include "fc_internal.h"
 
 #include <stdlib.h>
@@ -28,7 +30,7 @@ __device__ __forceinline__ int bag_of(const int64_t* __restrict__ offsets, int n
     return lo;
 }
 
-// key (and, on the first pass, value) of element i for the three sources
+// key of element i by source (SORT_SRC_RANKS is turned into slots by k_sort_hist first)
 template <int SRC>
 __device__ __forceinline__ int load_key(const int32_t* __restrict__ keys_in, int i, int limit, bool& bad) {
     if (SRC == SORT_SRC_SLOTS) return first_key(keys_in, i, limit, bad);

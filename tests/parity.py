@@ -315,17 +315,43 @@ def run_parity_lookahead(w, num_batches, warm=True, dma_evict=True, staging_rows
 
 
 def run_parity_planned(w, batches, warm=True, dma_evict=True, staging_rows=0, free_running=False, plan_first=False,
-                       dirty_tracking=False, forward_only=lambda t: False, log=None, inputs_ready=False, miss_dma=False):
+                       dirty_tracking=False, forward_only=lambda t: False, log=None, inputs_ready=False, miss_dma=False,
+                       ahead_miss_pct=100.0):
     """cache_plan_next: the index half of the next batch's prepare runs beside the current batch's forward / backward,
     rows move at cache_advance.  Same policy as plain cache_prepare, so the oracle is simply driven in program order.
-    batches: a count (the first ones) or a list of batch numbers, as for run_parity."""
+    batches: a count (the first ones) or a list of batch numbers, as for run_parity.
+    ahead_miss_pct: with inputs_ready the library runs ahead of the caller's stream while the previous batch's miss
+    share is below this (FC_AHEAD_MISS_PCT); 100 = always (the small test workloads miss far more than the library's
+    default of 2 in 100), None = the library's default, "median" = the median share of these very batches, so that
+    about every other batch runs ahead and the two modes keep alternating."""
+    import os
     import torch
     from oracle import Oracle
     from paper_2208_05321_amd import FreqCache
 
     dev = torch.device("cuda:0")
-    gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
-                    warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking, inputs_ready=inputs_ready, miss_dma=miss_dma)
+    if ahead_miss_pct == "median":
+        probe = Oracle(w.freq_rank, w.host_table(), w.cache_rows, warm=warm)
+        shares = []
+        for t in (range(batches) if isinstance(batches, int) else batches):
+            ids, offsets = w.batch(t)
+            probe.prepare(ids, offsets)
+            shares.append(100.0 * probe.stats()["n_miss"] / max(1.0, 0.5 * (len(ids) + len(offsets) - 1)))
+        probe.close()
+        ahead_miss_pct = float(np.median(shares[1:] or shares))
+        if log:
+            log(f"  miss shares {min(shares):.2f}..{max(shares):.2f} per 100, threshold {ahead_miss_pct:.2f}")
+    saved = os.environ.get("FC_AHEAD_MISS_PCT")
+    if ahead_miss_pct is not None:
+        os.environ["FC_AHEAD_MISS_PCT"] = repr(float(ahead_miss_pct))
+    try:                                             # the knob is read by cache_create
+        gpu = FreqCache(w.num_rows, w.dim, w.cache_rows, w.freq_rank, host_weight=None, staging_rows=staging_rows,
+                        warm=False, dma_evict=dma_evict, dirty_tracking=dirty_tracking, inputs_ready=inputs_ready, miss_dma=miss_dma)
+    finally:
+        if saved is None:
+            os.environ.pop("FC_AHEAD_MISS_PCT", None)
+        else:
+            os.environ["FC_AHEAD_MISS_PCT"] = saved
     host_gpu = gpu.host_weight()
     w.host_table(out=host_gpu)
     host_orc = host_gpu.copy()

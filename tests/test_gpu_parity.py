@@ -186,6 +186,18 @@ def test_planned_inputs_ready_tiny_cache_thrashing(torch_cuda, dma, free):
     run_parity_planned(w, 24, warm=False, dma_evict=dma, free_running=free, inputs_ready=True, staging_rows=16)
 
 
+@pytest.mark.parametrize("dma", [True, False])
+@pytest.mark.parametrize("free", [True, False])
+def test_planned_run_ahead_switches_on_and_off(torch_cuda, dma, free):
+    """FC_INPUTS_READY with the threshold at the median miss share of the very batches driven: about every other batch is
+    planned ahead of the caller's stream (index kernels unordered against it, the sort's later passes on the side stream),
+    the others behind it, and the two modes keep alternating."""
+    w = make_workload("c2", scale=0.1, cache_ratio=0.015)
+    run_parity_planned(w, 24, warm=True, dma_evict=dma, free_running=free, inputs_ready=True, ahead_miss_pct="median", log=log)
+    w = make_workload("c4", scale=0.02, cache_ratio=0.015)
+    run_parity_planned(w, 14, warm=True, dma_evict=dma, free_running=free, inputs_ready=True, ahead_miss_pct="median")
+
+
 @pytest.mark.parametrize("ready", [False, True])
 def test_planned_prepare_cold_and_small_blocks(torch_cuda, ready):
     w = make_workload("c2", scale=0.05, cache_ratio=0.05)

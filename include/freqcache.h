@@ -153,7 +153,8 @@ enum {
  *   FC_FWD_SORTED         0: batches with one lookup per bag are always pooled in bag order (default 1: in slot order, from
  *                         the pairs cache_prepare has sorted ahead of time for the backward pass, when those are at hand)
  *   FC_FWD_BAGS           bags per row-group of the bag-order forward kernel for one-lookup bags: 1, 2 or 4 (4)
- *   FC_SORT_BITS          most key bits per pass of a two-pass sort (11; read once per process)
+ *   FC_SORT_BITS          most key bits per pass of the backward's sort (4..11; default: two passes of up to 9 bits up to 18 key
+ *                         bits, beyond that passes of up to 9 bits without a scan kernel); FC_SORT_FUSED=0 keeps the scan kernel
  *   FC_FETCH_CU_MASK      experiment: number of compute units the early fetch's stream may use (default: all)
  *   FC_MARK_IPT           ids per thread of the marking kernel (2)
  *   FC_TUNE_REPORT        if set, cache_destroy prints where the early-fetch workgroup count settled

@@ -232,6 +232,8 @@ static int create(int64_t N, int32_t D, int64_t C, const int32_t* freq_rank, flo
     c->fill_blocks_early_max = c->fill_blocks_early;
     if (const char* e = getenv("FC_FWD_SORTED")) c->fwd_sorted = atoi(e) != 0;
     if (const char* e = getenv("FC_SORT_TAIL")) c->sort_tail_side = atoi(e) != 0;
+    if (const char* e = getenv("FC_SORT_BITS")) c->sort_max_bits = atoi(e);
+    if (const char* e = getenv("FC_SORT_FUSED")) c->sort_no_fuse = atoi(e) == 0;
     if (const char* e = getenv("FC_AHEAD_MISS_PCT")) { const float v = (float)atof(e); if (v >= 0.f) c->ahead_miss_pct = v; }
     if (const char* e = getenv("FC_FWD_BAGS")) { const int v = atoi(e); if (v == 1 || v == 2 || v == 4) c->fwd_bags = v; }
     if (const char* e = getenv("FC_MARK_IPT")) { const int v = atoi(e); if (v >= 1 && v <= 64) c->mark_ids_per_thread = v; }

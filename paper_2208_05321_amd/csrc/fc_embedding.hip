@@ -498,6 +498,7 @@ static int sort_pairs(fc_cache* c, SortBufs& sb, hipStream_t st, const int32_t* 
     j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
     j.one_per_bag = c->last_one_per_bag;      // sort_pairs serves the batch the last index half looked at
     j.tail_stream = tail; j.tail_event = c->ev_sort_tail; j.last_stream = last;
+    j.max_bits = c->sort_max_bits; j.no_fuse = c->sort_no_fuse;
     j.prof = c;
     return sort_in(j, sb, st, kres, vres);
 }
@@ -562,6 +563,7 @@ static int bwd_run(fc_cache* c, hipStream_t st, const int32_t* slots, int64_t n,
         SortJob j;
         j.src = SORT_SRC_SLOTS; j.keys_in = slots; j.offsets = offsets; j.num_bags = (int)num_bags; j.n = (int)n;
         j.limit = (int)c->C; j.bits = bits; j.flags = &c->ctl->async_flags;
+        j.max_bits = c->sort_max_bits; j.no_fuse = c->sort_no_fuse;
         j.prof = prof;
         FC_TRY(sort_in(j, sb, st, &kin, &vin));      // the scratch of the entry point that allocates nothing has no supertile tables: scan kernels there
     }

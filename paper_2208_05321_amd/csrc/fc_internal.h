@@ -129,6 +129,7 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    int sort_max_bits = 0; bool sort_no_fuse = false;   // tuning: FC_SORT_BITS, FC_SORT_FUSED=0
     float ahead_miss_pct = 2.0f;    // FC_INPUTS_READY: run ahead while the previous batch's misses stay below this share (tuning: FC_AHEAD_MISS_PCT)
     bool ahead_now = false;         // the cache_plan_next in progress runs ahead of the caller's stream
     bool sort_tail_side = true;     // cache_plan_next: the sort's passes after the first run on the side stream (tuning: FC_SORT_TAIL=0)
@@ -353,6 +354,7 @@ struct SortJob {
     bool one_per_bag = false;                  // SORT_SRC_SLOTS / _RANKS: the caller knows that offsets[b] == b for every bag
     const int32_t* rank_slot = nullptr; int32_t* slots_out = nullptr;     // SORT_SRC_RANKS
     int n = 0, limit = 0, bits = 1;
+    int max_bits = 0; bool no_fuse = false;    // experiments: most bits per pass (0 = the default policy), never skip the scan kernel
     uint32_t* flags = nullptr;                 // device word for EF_BAD_SLOT, may be null
     int32_t *keysA = nullptr, *valsA = nullptr, *keysB = nullptr, *valsB = nullptr;   // n ints each
     int32_t *ghist = nullptr, *dtot = nullptr; // (tiles << RS_MAX_BITS) ints, (1 << RS_MAX_BITS) ints

@@ -328,22 +328,15 @@ static int run_passes(const SortJob& j, hipStream_t st, int passes, int rb, int3
     return FC_OK;
 }
 
-static int env_int(const char* name, int lo, int hi, int dflt) {
-    const char* e = getenv(name);
-    if (!e) return dflt;
-    const int v = atoi(e);
-    return (v >= lo && v <= hi) ? v : dflt;
-}
-
 int radix_sort(const SortJob& j, hipStream_t st, const int32_t** kres, const int32_t** vres) {
     // Every pass is a chain of short launches bound by latency rather than by bytes.  Batches of up to FUSE_MAX_TILES
     // tiles and more than 18 key bits take passes of at most 9 bits, each two launches (counts, then offsets and scatter in
     // one kernel; the per-supertile counts make the scan in between unnecessary; the caller supplies their table); 7-bit digits leave runs of 16 keys per digit and tile,
     // i.e. whole sectors to write, where 11-bit digits left single keys.  Larger jobs (the static module's ranking) keep
     // the scan kernel: two passes up to 22 key bits, beyond that passes of at most 8 bits.
-    // (FC_SORT_BITS, FC_SORT_FUSED: read once per process, for experiments.)
-    static const int env_bits = env_int("FC_SORT_BITS", 4, RS_TWO_PASS_BITS, 0);
-    static const int env_fused = env_int("FC_SORT_FUSED", 0, 1, 1);
+    // (j.max_bits / j.no_fuse, from FC_SORT_BITS / FC_SORT_FUSED at cache_create, override this for experiments.)
+    const int env_bits = (j.max_bits >= 4 && j.max_bits <= RS_TWO_PASS_BITS) ? j.max_bits : 0;
+    const bool env_fused = !j.no_fuse;
     const int64_t nblk = cdiv(j.n, RS_TILE);
     int passes, rb;
     // up to 18 key bits two passes with a scan kernel each are the shorter chain (measured at 426 k pairs of 18 bits)

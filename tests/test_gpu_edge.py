@@ -67,6 +67,20 @@ def test_large_cache_many_key_bits(torch_cuda, multi_hot, cache_rows):
     run_parity(w, 3, warm=True)
 
 
+@pytest.mark.parametrize("knobs", [{"FC_SORT_BITS": "4"}, {"FC_SORT_BITS": "6"}, {"FC_SORT_BITS": "9"}, {"FC_SORT_FUSED": "0"},
+                                   {"FC_SORT_FUSED": "0", "FC_SORT_BITS": "5"}])
+def test_sort_pass_shapes(torch_cuda, monkeypatch, knobs):
+    """Every shape of the sort's passes on one cheap workload: 2 to 5 passes, digits of 4 to 11 bits, with and without the
+    scan kernel (the knobs override the policy that picks among them by key width and batch size)."""
+    for k, v in knobs.items():
+        monkeypatch.setenv(k, v)
+    w = TinyWorkload(num_rows=90000, dim=8, cache_rows=40000, seed=53, multi_hot=True, bags=5000, max_bag=6, hot=[1, 2, 3],
+                     distinct_cap=3000)
+    run_parity(w, 3, warm=True)
+    w = TinyWorkload(num_rows=90000, dim=8, cache_rows=40000, seed=54, multi_hot=False, bags=21000, hot=[9], distinct_cap=3000)
+    run_parity(w, 3, warm=False)
+
+
 def test_large_cache_batches_of_very_different_sizes(torch_cuda):
     """Consecutive sorts of very different sizes on one handle (the tables of per-supertile counts alternate, and each
     sort clears what the one before it left behind): 70k lookups, then 5, then 23k, ..., trained and compared every time."""

@@ -38,11 +38,10 @@ void prof_collect(fc_cache* c) {
     if (c->pre) (void)hipStreamSynchronize(c->pre);
     // FC_TIMELINE=<file>: besides the totals, every span's start and end in us since the first span of this collection,
     // one "name start end" line each (which kernels really run side by side, and what waits for what)
-    static FILE* timeline = nullptr;
-    static std::string timeline_path;
+    FILE*& timeline = c->timeline;          // per handle: two caches in one process keep separate files
     const char* want = getenv("FC_TIMELINE");
-    if (timeline && (!want || timeline_path != want)) { fclose(timeline); timeline = nullptr; }
-    if (!timeline && want && *want) { timeline = fopen(want, "w"); timeline_path = want; }
+    if (timeline && (!want || c->timeline_path != want)) { fclose(timeline); timeline = nullptr; }
+    if (!timeline && want && *want) { timeline = fopen(want, "w"); c->timeline_path = want; }
     if (timeline && !c->spans.empty()) fprintf(timeline, "# %zu spans\n", c->spans.size());
     for (const ProfSpan& sp : c->spans) {
         float ms = 0.f;
@@ -114,6 +113,7 @@ static void destroy(fc_cache* c) {
     if (c->tune_early && getenv("FC_TUNE_REPORT"))
         fprintf(stderr, "freqcache: early-fetch workgroups settled at %d (fetch / copy ratio %.3f)\n", c->fill_blocks_early, c->tune_ratio);
     (void)hipSetDevice(c->device);
+    if (c->timeline) { fclose(c->timeline); c->timeline = nullptr; }
     (void)gather_wait(c);              // no gather thread is about to enqueue a copy
     if (c->stream || c->side) (void)hipDeviceSynchronize();
     gather_destroy(c);

@@ -3,6 +3,8 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <string>
 #include <vector>
 
 #include "../../include/freqcache.h"
@@ -129,6 +131,7 @@ struct fc_cache {
     uint32_t* pbits = nullptr;      // rank-space bitmap: rows of the previously prepared batch
     hipEvent_t ev_evict_done = nullptr, ev_gather_done = nullptr;
     bool evict_pending = false;
+    FILE* timeline = nullptr; std::string timeline_path;   // FC_TIMELINE: where cache_profile_get writes every span's start and end
     int sort_max_bits = 0; bool sort_no_fuse = false;   // tuning: FC_SORT_BITS, FC_SORT_FUSED=0
     float ahead_miss_pct = 2.0f;    // FC_INPUTS_READY: run ahead while the previous batch's misses stay below this share (tuning: FC_AHEAD_MISS_PCT)
     bool ahead_now = false;         // the cache_plan_next in progress runs ahead of the caller's stream

@@ -5,7 +5,8 @@
   run against those builds in a child process (the sanitizer runtime has to be loaded before the interpreter starts).
 * ThreadSanitizer: the scatter pool of the DMA evict transmitter (csrc/scatter_pool.h: publish / in-order completion /
   wait / buffer reuse) is built without any GPU runtime, with a mocked "block has landed" signal, and run under
-  -fsanitize=thread (tests/tsan_scatter_pool.cpp checks ordering and the final table as well).
+  -fsanitize=thread (tests/tsan_scatter_pool.cpp checks ordering and the final table as well), and so are the host
+  threads of the DMA miss path (csrc/gather_pool.h, tests/tsan_gather_pool.cpp).
 """
 import os
 import subprocess
@@ -43,6 +44,26 @@ def test_oracle_and_fill_under_asan_ubsan(tmp_path):
     assert r.returncode == 0, tail
     assert "AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, tail
     assert " passed" in r.stdout, tail
+
+
+def test_gather_pool_under_tsan(tmp_path):
+    """The host threads of the DMA miss path (csrc/gather_pool.h) with mocked copies: every row gathered once and sent once,
+    a chunk sent only when complete, one arrival mark per job and after every send, failures reported once."""
+    exe = str(tmp_path / "tsan_gather_pool")
+    src = os.path.join(ROOT, "tests", "tsan_gather_pool.cpp")
+    inc = os.path.join(ROOT, "paper_2208_05321_amd", "csrc")
+    c = subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=thread", "-pthread", "-I", inc, src, "-o", exe],
+                       capture_output=True, text=True)
+    if c.returncode != 0 and "tsan" in c.stderr.lower():
+        pytest.skip("no libtsan in this toolchain")
+    assert c.returncode == 0, c.stderr[-2000:]
+    for jobs, threads in ((200, 6), (120, 3), (60, 1)):
+        r = subprocess.run([exe, str(jobs), str(threads)], capture_output=True, text=True, timeout=300,
+                           env=dict(os.environ, TSAN_OPTIONS="halt_on_error=1"))
+        if "unexpected memory mapping" in r.stderr:
+            pytest.skip("ThreadSanitizer cannot map its shadow memory on this kernel")
+        assert r.returncode == 0 and "ThreadSanitizer" not in r.stderr, (r.stdout + r.stderr)[-3000:]
+        assert r.stdout.startswith("ok:")
 
 
 def test_scatter_pool_under_tsan(tmp_path):
